@@ -1,0 +1,105 @@
+/*
+ * ie_attn — exact softmax attention, forward and backward, for one GPU's share of the
+ * heads over the full sequence (MI355X / gfx950).
+ *
+ * This is the per-GPU step of hybrid sequence parallelism: after the first all-to-all
+ * every GPU holds Q, K and V of all S tokens for heads/s_sp heads, laid out
+ * [B, S, heads_local, head_dim] (Sec. 2.2 "SP-2", Sec. 3.1 "Sequence Parallelism"), and
+ * runs fused multi-head attention on them (Sec. 2.1 "Transformer Architecture";
+ * Sec. 4.2 "Computation Profiler": self-atten(b, S, H, D/s_sp) on a single GPU).  The
+ * backward pass recomputes the probabilities instead of storing them (Sec. 3.1: the
+ * fused kernel includes selective activation recomputation), so only o and the
+ * per-row log-sum-exp travel from forward to backward.
+ *
+ * Definition (batch b, query head h, kv head g = h / (Hq/Hkv), token i in document
+ * [a, e); the visible keys are a <= j <= i when causal, a <= j < e otherwise):
+ *     s_ij  = scale * <q[b,i,h,:], k[b,j,g,:]>
+ *     lse_i = ln sum_j exp(s_ij)            p_ij = exp(s_ij - lse_i)
+ *     o[b,i,h,:] = sum_j p_ij v[b,j,g,:]
+ *     delta_i = <dout[b,i,h,:], o[b,i,h,:]>     ds_ij = p_ij (<dout_i, v_j> - delta_i)
+ *     dq_i = scale sum_j ds_ij k_j
+ *     dk_j = scale sum_{h in group g} sum_i ds_ij q_i      dv_j = sum_{h in g} sum_i p_ij dout_i
+ *
+ * Common conventions
+ *   - Every pointer is a DEVICE pointer on the current HIP device; the caller owns all
+ *     buffers.  The library keeps no state and never synchronises with the host: all
+ *     work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and the buffers must stay alive until the stream has passed it.
+ *   - q, o, dout, dq : contiguous [B, S, Hq,  D] bf16.
+ *     k, v, dk, dv   : contiguous [B, S, Hkv, D] bf16.
+ *     lse            : contiguous [B, Hq, S] fp32, natural log, `scale` included.
+ *   - bf16 outputs are rounded to nearest even from fp32 accumulators.
+ *   - Packed documents: cu_seqlens != NULL is an int32 device array of num_docs+1
+ *     non-decreasing offsets with cu_seqlens[0] = 0 and cu_seqlens[num_docs] = S; B must
+ *     be 1; tokens attend only inside their own document (block-diagonal mask);
+ *     empty documents are allowed.  The array's contents are not read on the host and
+ *     are therefore not validated; offsets outside [0, S] give undefined results.
+ *     cu_seqlens == NULL (num_docs ignored) means one document per batch entry.
+ *   - Supported: D in {64, 128}; Hq % Hkv == 0; scale finite and > 0; causal in {0, 1};
+ *     any S >= 1 with B*S*Hq*D < 2^40 elements.
+ *   - Return value: 0 on success or a negative ie_attn_status; nothing is printed and
+ *     no exception crosses the boundary.  On error no kernel has been launched, except
+ *     for IE_ERR_HIP, which reports a failed launch part-way through a call.
+ */
+#ifndef IE_ATTN_H
+#define IE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ie_attn_status {
+  IE_OK = 0,
+  IE_ERR_NULL = -1,        /* a required pointer is NULL */
+  IE_ERR_SHAPE = -2,       /* B, S, Hq, Hkv <= 0; Hq % Hkv != 0; packed with B != 1 or num_docs < 1; size too large */
+  IE_ERR_UNSUPPORTED = -3, /* D not in {64,128}; scale not finite or <= 0; causal not 0/1 */
+  IE_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned (256 B) or smaller than ie_attn_bwd_workspace_bytes */
+  IE_ERR_HIP = -5          /* a HIP call failed; ie_attn_last_hip_error() has the runtime's text */
+} ie_attn_status;
+
+/*
+ * Forward: writes o and lse for every token (steps "S = QK^T, mask, online softmax,
+ * O = PV" of fused attention; Sec. 2.1, Sec. 4.2).  Both outputs are fully overwritten.
+ */
+int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                const int32_t* cu_seqlens, int32_t num_docs,
+                int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
+                float scale, int32_t causal, void* stream);
+
+/*
+ * Bytes of device workspace ie_attn_bwd needs for this shape (delta [B,Hq,S] fp32, the
+ * fp32 dq accumulator [B,S,Hq,D], fp32 dk/dv accumulators when Hq != Hkv).  Returns 0
+ * for an invalid shape.  Pure host arithmetic; touches no device.
+ */
+size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs);
+
+/*
+ * Backward: given dout and the forward's o and lse, writes dq, dk, dv (fully
+ * overwritten; dk/dv are summed over the Hq/Hkv query heads of each kv head).  The
+ * probabilities are recomputed from lse (Sec. 3.1), backward costs 2.5x the forward's
+ * matrix work (cf. Sec. 4.3: backward is about twice as compute-intensive as forward).
+ * `workspace` is caller-owned scratch of at least ie_attn_bwd_workspace_bytes(...) bytes,
+ * 256-byte aligned; the library zero-fills what it needs on `stream`, its contents
+ * after the call are unspecified.  dq is accumulated with fp32 atomics, so its last bits
+ * may differ from run to run.
+ */
+int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                const float* lse, void* dq, void* dk, void* dv,
+                const int32_t* cu_seqlens, int32_t num_docs,
+                int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
+                float scale, int32_t causal,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static text for a status code (never NULL). */
+const char* ie_attn_strerror(int code);
+
+/* Text of the HIP error behind the calling thread's most recent IE_ERR_HIP ("" if none). */
+const char* ie_attn_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IE_ATTN_H */

@@ -1,0 +1,221 @@
+// Device-side building blocks shared by the gfx950 attention kernels: vector types, the
+// MFMA wrappers with their operand layouts, the swizzled LDS tile layout, tile loaders
+// and the mapping from a workgroup index to (batch, head, document, tile).
+//
+// MFMA operand layouts used throughout (wave64, lane l, h = l / 32):
+//   v_mfma_f32_32x32x16_bf16  C[m][n] += sum_k A[m][k] * B[k][n]
+//     A: lane holds row m = l % 32, k = 8h .. 8h+7           (8 bf16)
+//     B: lane holds col n = l % 32, k = 8h .. 8h+7           (8 bf16)
+//     C: lane holds col n = l % 32; register r (0..15) is row m = 8 (r / 4) + 4h + r % 4
+//   Because C keeps one column per lane and spreads rows over registers, a product
+//   whose ROW index is the next contraction index can feed the next MFMA's B operand
+//   straight from registers: registers 8s .. 8s+7 of C are rows
+//   {16s + 4h + 0..3, 16s + 8 + 4h + 0..3}, which is the k-slot order the A operand of
+//   the second product has to follow.
+//   ds_read_b64_tr_b16 (LDS transpose load): inside each group of 16 lanes, lane i
+//   receives element (i % 4) of the 64-bit words addressed by lanes i/4, 4 + i/4,
+//   8 + i/4 and 12 + i/4.  With lane L addressing row r0 + L/4, columns c0 + 4 (L%4)..+3
+//   of a row-major tile, lane i gets rows r0 .. r0+3 of column c0 + i: a column gather,
+//   which is what an MFMA operand needs when the contraction runs over tile rows.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ie {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;   // 4 wavefronts per workgroup
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct AttnParams {
+  const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* dout;
+  __bf16* o_out; float* lse_out;
+  const float* lse; float* delta;
+  __bf16* dq; __bf16* dk; __bf16* dv;
+  const int32_t* cu; int32_t num_docs;
+  int64_t B, S;
+  int32_t Hq, Hkv;
+  float scale, scale_log2;  // scale_log2 = scale * log2(e)
+  int32_t causal;
+  int32_t tiles;            // tiles per head the grid was sized for (upper bound when packed)
+};
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Exchange between the two half-waves with v_permlane32_swap: given (a, b) it returns
+// r0 = {a[0..31], b[0..31]} and r1 = {a[32..63], b[32..63]}.  With a == b == x, lane l
+// sees x[l] and x[l ^ 32] in (r0, r1) (in some order).  The vector elements are copied to
+// scalars before the bit cast: a bit cast applied to `r[1]` directly reads element 0.
+__device__ __forceinline__ void halfwave_pair(float x, float& r0, float& r1) {
+  const uint32_t a = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+  const uint32_t u0 = r[0], u1 = r[1];
+  r0 = __builtin_bit_cast(float, u0);
+  r1 = __builtin_bit_cast(float, u1);
+}
+// Maximum / sum over the two half-waves: lane l and lane l ^ 32 both end up with the result.
+__device__ __forceinline__ float halfwave_max(float x) {
+  float r0, r1;
+  halfwave_pair(x, r0, r1);
+  return fmaxf(r0, r1);
+}
+__device__ __forceinline__ float halfwave_sum(float x) {
+  float r0, r1;
+  halfwave_pair(x, r0, r1);
+  return r0 + r1;
+}
+
+// ---- LDS tile layout -------------------------------------------------------------------
+// A tile is ROWS x D bf16, row pitch D*2 bytes, no padding.  The 16-byte chunk c of row r
+// sits at chunk position c ^ swz(r), which keeps both access patterns spread over the
+// banks: 16 lanes reading the same chunk of 16 consecutive rows (MFMA operand rows), and
+// the transpose loads that read 4 consecutive rows x 64 contiguous bytes.
+template <int D>
+__device__ __forceinline__ int swz(int r) {
+  int f = ((r & 3) << 2) | (((r >> 2) ^ r) & 3);
+  return f & (D / 8 - 1);
+}
+template <int D>
+__device__ __forceinline__ int tile_off(int r, int chunk) {  // byte offset of 16-byte chunk
+  return r * (D * 2) + ((chunk ^ swz<D>(r)) << 4);
+}
+
+__device__ __forceinline__ bf16x8 lds_read8(const char* base, int off) {
+  return *reinterpret_cast<const bf16x8*>(base + off);
+}
+
+// Transpose load: returns 4 bf16 = rows r0..r0+3 (see header) of this lane's column.
+__device__ __forceinline__ bf16x4 lds_read_tr4(const char* p) {
+  typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+  i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p));
+  return __builtin_bit_cast(bf16x4, v);
+}
+__device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b) {
+  return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Byte offset this lane passes to the transpose load so that, for a tile in the swizzled
+// layout, it receives rows r0 + {0..3} of column (c0 + lane % 16), where c0 is a multiple of 16.
+template <int D>
+__device__ __forceinline__ int tr_off(int lane, int r0, int c0) {
+  int L = lane & 15;
+  int row = r0 + (L >> 2);
+  int col = c0 + ((L & 3) << 2);
+  return row * (D * 2) + (((col >> 3) ^ swz<D>(row)) << 4) + ((col & 4) << 1);
+}
+
+// ---- global -> register -> LDS tile copies --------------------------------------------
+// A ROWS x D tile is ROWS * D/8 chunks of 16 bytes; thread t owns chunks t, t+256, ...
+template <int ROWS, int D>
+struct TileRegs {
+  static constexpr int N = ROWS * (D / 8) / kThreads;
+  u32x4 r[N];
+};
+
+// Rows row0 .. row0+ROWS-1 of a [*, heads, D] tensor (head already folded into `base`,
+// row stride `stride` elements); rows past row_last are clamped to row_last so that no
+// load leaves the tensor (their values are masked by the caller).
+template <int ROWS, int D>
+__device__ __forceinline__ void tile_load(TileRegs<ROWS, D>& t, const __bf16* base, int64_t stride,
+                                          int64_t row0, int64_t row_last, int tid) {
+#pragma unroll
+  for (int i = 0; i < TileRegs<ROWS, D>::N; ++i) {
+    int c = tid + i * kThreads;
+    int r = c / (D / 8), ch = c % (D / 8);
+    int64_t row = row0 + r;
+    row = row < row_last ? row : row_last;
+    t.r[i] = *reinterpret_cast<const u32x4*>(base + row * stride + ch * 8);
+  }
+}
+template <int ROWS, int D>
+__device__ __forceinline__ void tile_store(const TileRegs<ROWS, D>& t, char* lds, int tid) {
+#pragma unroll
+  for (int i = 0; i < TileRegs<ROWS, D>::N; ++i) {
+    int c = tid + i * kThreads;
+    int r = c / (D / 8), ch = c % (D / 8);
+    *reinterpret_cast<u32x4*>(lds + tile_off<D>(r, ch)) = t.r[i];
+  }
+}
+
+// ---- workgroup -> (batch, head, document, tile) ----------------------------------------
+struct TileCoord {
+  int b, h;
+  int64_t doc_begin, doc_end;  // token range of the document
+  int64_t t0;                  // first token of the tile
+  bool valid;
+};
+
+// Tiles of `TS` tokens never straddle documents.  Work item w = blockIdx.x is decoded as
+// head = w % (B*H) and tile = tiles-1 - w / (B*H): consecutive workgroups (which the
+// hardware deals round-robin to the 8 XCDs) belong to different heads, so with B*H a
+// multiple of 8 each head's K/V stream stays inside one XCD's L2; `heavy_last` says
+// whether high tile numbers carry the most work (forward and dq: causal rows late in a
+// document see more keys) so that the heaviest tiles are dispatched first.
+template <int TS>
+__device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads, bool heavy_last, int* scratch) {
+  TileCoord c;
+  int nH = (int)p.B * heads;
+  int w = blockIdx.x;
+  int hh = w % nH;
+  int t = w / nH;
+  if (heavy_last) t = p.tiles - 1 - t;
+  c.b = hh / heads;
+  c.h = hh % heads;
+  if (p.cu == nullptr) {
+    c.doc_begin = 0;
+    c.doc_end = p.S;
+    c.t0 = (int64_t)t * TS;
+    c.valid = c.t0 < p.S;
+    return c;
+  }
+  // Packed: find the document whose tile range contains t.  Thread i counts the tiles of
+  // documents i, i+256, ... in rounds of 256 documents with a block-wide scan per round.
+  int tid = threadIdx.x;
+  int lane = tid & 63, wv = tid >> 6;
+  int* s_wave = scratch;       // [4] wave totals
+  int* s_res = scratch + 4;    // [0] doc index or -1, [1] tiles before that doc
+  if (tid == 0) { s_res[0] = -1; s_res[1] = 0; }
+  __syncthreads();
+  int before = 0;  // tiles of all documents in earlier rounds
+  for (int base = 0; base < p.num_docs; base += kThreads) {
+    int d = base + tid;
+    int nt = 0;
+    if (d < p.num_docs) nt = (p.cu[d + 1] - p.cu[d] + TS - 1) / TS;
+    int inc = nt;  // inclusive scan inside the wave
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      int y = __shfl_up(inc, s, 64);
+      if (lane >= s) inc += y;
+    }
+    if (lane == 63) s_wave[wv] = inc;
+    __syncthreads();
+    int woff = 0, total = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { int x = s_wave[i]; if (i < wv) woff += x; total += x; }
+    int excl = before + woff + inc - nt;
+    if (nt > 0 && t >= excl && t < excl + nt) { s_res[0] = d; s_res[1] = excl; }
+    __syncthreads();
+    before += total;
+    if (s_res[0] >= 0 || t < before) break;
+  }
+  __syncthreads();
+  int d = s_res[0];
+  if (d < 0) { c.valid = false; c.doc_begin = c.doc_end = c.t0 = 0; return c; }
+  c.doc_begin = p.cu[d];
+  c.doc_end = p.cu[d + 1];
+  c.t0 = c.doc_begin + (int64_t)(t - s_res[1]) * TS;
+  c.valid = true;
+  return c;
+}
+
+}  // namespace ie

@@ -1,0 +1,119 @@
+// C-ABI entry points (include/ie_attn.h): argument validation, workspace carving and
+// kernel launches.  Host code only decides shapes and grids; every step of the path
+// runs in the kernels of attn_fwd.hip / attn_bwd.hip.
+#include "../../include/ie_attn.h"
+
+#include <cmath>
+#include <cstring>
+
+#include "attn_common.hpp"
+#include "launch.hpp"
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+constexpr int64_t kMaxElems = (int64_t)1 << 40;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+ie::AttnParams base_params(const int32_t* cu, int32_t num_docs, int64_t B, int64_t S, int32_t Hq, int32_t Hkv,
+                           float scale, int32_t causal) {
+  ie::AttnParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.cu = cu;
+  p.num_docs = cu ? num_docs : 0;
+  p.B = B; p.S = S; p.Hq = Hq; p.Hkv = Hkv;
+  p.scale = scale;
+  p.scale_log2 = scale * ie::kLog2e;
+  p.causal = causal;
+  return p;
+}
+
+int check_shape(const int32_t* cu, int32_t num_docs, int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
+                float scale, int32_t causal) {
+  if (B <= 0 || S <= 0 || Hq <= 0 || Hkv <= 0) return IE_ERR_SHAPE;
+  if (Hq % Hkv != 0) return IE_ERR_SHAPE;
+  if (cu != nullptr && (B != 1 || num_docs < 1)) return IE_ERR_SHAPE;
+  if (D != 64 && D != 128) return IE_ERR_UNSUPPORTED;
+  if (!(scale > 0.0f) || !std::isfinite(scale)) return IE_ERR_UNSUPPORTED;
+  if (causal != 0 && causal != 1) return IE_ERR_UNSUPPORTED;
+  // element counts must stay far from overflow and the grid below 2^31
+  if (B > kMaxElems / S || B * S > kMaxElems / Hq || B * S * Hq > kMaxElems / D) return IE_ERR_SHAPE;
+  if (S >= ((int64_t)1 << 31)) return IE_ERR_SHAPE;
+  return IE_OK;
+}
+
+}  // namespace
+
+namespace ie {
+int hip_fail(hipError_t e) {
+  std::strncpy(g_hip_error, hipGetErrorString(e), sizeof(g_hip_error) - 1);
+  g_hip_error[sizeof(g_hip_error) - 1] = 0;
+  return IE_ERR_HIP;
+}
+}  // namespace ie
+
+extern "C" {
+
+int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* cu_seqlens,
+                int32_t num_docs, int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale,
+                int32_t causal, void* stream) {
+  if (!q || !k || !v || !o || !lse) return IE_ERR_NULL;
+  int rc = check_shape(cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal);
+  if (rc) return rc;
+  ie::AttnParams p = base_params(cu_seqlens, num_docs, B, S, Hq, Hkv, scale, causal);
+  p.q = static_cast<const __bf16*>(q);
+  p.k = static_cast<const __bf16*>(k);
+  p.v = static_cast<const __bf16*>(v);
+  p.o_out = static_cast<__bf16*>(o);
+  p.lse_out = lse;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return ie::launch_fwd(p, D, st);
+}
+
+size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs) {
+  (void)num_docs;
+  if (check_shape(nullptr, 0, B, S, Hq, Hkv, D, 1.0f, 1) != IE_OK) return 0;
+  return align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256);  // delta [B,Hq,S]
+}
+
+int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                void* dq, void* dk, void* dv, const int32_t* cu_seqlens, int32_t num_docs, int64_t B, int64_t S,
+                int32_t Hq, int32_t Hkv, int32_t D, float scale, int32_t causal, void* workspace,
+                size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return IE_ERR_NULL;
+  int rc = check_shape(cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal);
+  if (rc) return rc;
+  size_t need = ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < need) return IE_ERR_WORKSPACE;
+  ie::AttnParams p = base_params(cu_seqlens, num_docs, B, S, Hq, Hkv, scale, causal);
+  p.q = static_cast<const __bf16*>(q);
+  p.k = static_cast<const __bf16*>(k);
+  p.v = static_cast<const __bf16*>(v);
+  p.o = static_cast<const __bf16*>(o);
+  p.dout = static_cast<const __bf16*>(dout);
+  p.lse = lse;
+  p.delta = static_cast<float*>(workspace);
+  p.dq = static_cast<__bf16*>(dq);
+  p.dk = static_cast<__bf16*>(dk);
+  p.dv = static_cast<__bf16*>(dv);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return ie::launch_bwd(p, D, st);
+}
+
+const char* ie_attn_strerror(int code) {
+  switch (code) {
+    case IE_OK: return "success";
+    case IE_ERR_NULL: return "a required pointer is NULL";
+    case IE_ERR_SHAPE: return "invalid shape (sizes must be positive, Hq % Hkv == 0, packed input needs B == 1 and num_docs >= 1)";
+    case IE_ERR_UNSUPPORTED: return "unsupported configuration (D must be 64 or 128, scale finite and > 0, causal 0 or 1)";
+    case IE_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
+    case IE_ERR_HIP: return "a HIP runtime call failed";
+    default: return "unknown ie_attn status";
+  }
+}
+
+const char* ie_attn_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

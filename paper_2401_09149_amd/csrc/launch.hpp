@@ -1,0 +1,32 @@
+// Host-side launchers, one per kernel file, called by the C-ABI entry points.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "attn_common.hpp"
+
+namespace ie {
+
+// Records the HIP error text for ie_attn_last_hip_error() and returns IE_ERR_HIP.
+int hip_fail(hipError_t e);
+
+int launch_fwd(AttnParams p, int D, hipStream_t st);
+int launch_bwd(AttnParams p, int D, hipStream_t st);
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Number of `ts`-token tiles per head the grid must cover (upper bound when packed:
+// every document adds at most one partial tile).
+inline int64_t tiles_per_head(int64_t S, int64_t ts, const int32_t* cu, int32_t num_docs) {
+  return cu ? S / ts + num_docs : ceil_div(S, ts);
+}
+
+constexpr int kErrShape = -2;  // IE_ERR_SHAPE
+
+template <typename K>
+inline int set_smem(K kernel, int bytes) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  return e == hipSuccess ? 0 : hip_fail(e);
+}
+
+}  // namespace ie

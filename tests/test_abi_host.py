@@ -1,0 +1,74 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2401_09149_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2401_09149_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ie_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ie_attn_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2401_09149_amd import binding
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror_is_total(lib):
+    seen = set()
+    for code in range(-7, 2):
+        s = lib.ie_attn_strerror(code)
+        assert s and len(s) > 0
+        seen.add(s)
+    assert len(seen) >= 7   # six statuses + "unknown"
+
+
+def test_workspace_query(lib):
+    f = lib.ie_attn_bwd_workspace_bytes
+    n = f(1, 32768, 32, 32, 128, 0)
+    assert n >= 32768 * 32 * 4 and n % 256 == 0
+    assert f(1, 0, 32, 32, 128, 0) == 0          # invalid shapes report 0
+    assert f(1, 128, 3, 2, 128, 0) == 0
+    assert f(1, 128, 4, 2, 96, 0) == 0
+
+
+def test_bad_arguments_fail_before_any_launch(lib):
+    one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    args = dict(B=1, S=128, Hq=4, Hkv=2, D=128, scale=0.1, causal=1)
+
+    def fwd(q=one, k=one, v=one, o=one, lse=one, cu=None, nd=0, **kw):
+        a = dict(args, **kw)
+        return lib.ie_attn_fwd(q, k, v, o, lse, cu, nd, a["B"], a["S"], a["Hq"], a["Hkv"], a["D"], a["scale"], a["causal"], None)
+
+    assert fwd(q=None) == -1 and fwd(lse=None) == -1
+    assert fwd(S=0) == -2 and fwd(Hq=3) == -2 and fwd(B=-1) == -2
+    assert fwd(cu=one, nd=3, B=2) == -2 and fwd(cu=one, nd=0) == -2
+    assert fwd(D=96) == -3 and fwd(scale=0.0) == -3 and fwd(scale=float("nan")) == -3 and fwd(causal=2) == -3
+    assert fwd(S=2 ** 40) == -2
+
+    def bwd(ws=one, ws_bytes=1 << 30, dq=one, **kw):
+        a = dict(args, **kw)
+        return lib.ie_attn_bwd(one, one, one, one, one, one, dq, one, one, None, 0, a["B"], a["S"], a["Hq"], a["Hkv"],
+                               a["D"], a["scale"], a["causal"], ws, ws_bytes, None)
+
+    assert bwd(dq=None) == -1
+    assert bwd(ws=None) == -4 and bwd(ws_bytes=16) == -4 and bwd(ws=ctypes.c_void_p(264)) == -4
+    assert bwd(D=32) == -3
