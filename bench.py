@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention hot path on one MI355X.
+
+A step is one pass of the whole path (forward, then backward: delta, dQ, dK/dV) over one
+batch of seeded synthetic input that is already resident in HBM.  The workload is the
+7B-class layer with all heads on one GPU: B=1, S=32768, Hq=Hkv=32, D=128, causal, bf16.
+FLOP convention: forward = 4*S^2*D*Hq / 2 (causal halving), backward = 2.5x forward.
+
+Prints ONE JSON line.  `value` is fwd+bwd TFLOP/s; `roofline` describes the kernel that
+takes the most time, measured live with events on the launch stream; `cpu_baseline` times
+the fp64 oracle on the host cores on a bounded sample of the same inputs.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz = 2516.6
+
+
+def event_ms(fn, iters):
+    import torch
+    start = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    stop = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    for i in range(iters):
+        start[i].record()
+        fn()
+        stop[i].record()
+    torch.cuda.synchronize()
+    ts = [a.elapsed_time(b) for a, b in zip(start, stop)]
+    return sum(ts) / len(ts), min(ts)
+
+
+def cpu_baseline(cfg, q, k, v, dout, prefix, heads):
+    """fp64 oracle, all three passes, on the causal prefix [0, prefix) of the first `heads` heads."""
+    import numpy as np
+    import torch
+    from oracle import attention as ora
+    ora.build()
+    sl = lambda t, hcount: np.ascontiguousarray(
+        t[:, :prefix, :hcount].to("cpu", torch.float32).numpy().astype(np.float64))
+    kv_heads = max(1, heads * cfg.Hkv // cfg.Hq)
+    q64, k64, v64, do64 = sl(q, heads), sl(k, kv_heads), sl(v, kv_heads), sl(dout, heads)
+    t0 = time.perf_counter()
+    ora.attn_fwd_bwd(q64, k64, v64, do64, cfg.scale, True)
+    dt = time.perf_counter() - t0
+    flop = 3.5 * 2.0 * float(prefix) ** 2 * cfg.D * heads
+    return {
+        "value": flop / dt / 1e12,
+        "unit": "TFLOP/s",
+        "cores": ora.num_threads(),
+        "kind": "oracle",
+        "seconds": dt,
+        "sample": f"fp64 oracle fwd+bwd (3 passes) on tokens [0,{prefix}) of q heads 0..{heads - 1} of the same "
+                  f"seeded inputs (a self-contained causal prefix), same FLOP convention",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="index into the workload table (default: the headline config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-prefix", type=int, default=32768)
+    ap.add_argument("--cpu-heads", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2401_09149_amd import binding, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    binding.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config]
+    cu_np = W.make_cu_seqlens(cfg)
+    cu = None if cu_np is None else torch.tensor(cu_np, dtype=torch.int32, device=dev)
+    q, k, v, dout = W.make_inputs(cfg, device=dev)
+    o = torch.empty_like(q)
+    lse = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device=dev)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = binding.alloc_bwd_workspace(q, k, cu)
+
+    def fwd():
+        binding.ie_attn_fwd(q, k, v, o, lse, cu, cfg.scale, cfg.causal)
+
+    def bwd(phases=binding.BWD_ALL):
+        binding.ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu, cfg.scale, cfg.causal, ws, phases)
+
+    def step():
+        fwd()
+        bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # Per-kernel durations, events on the launch stream (torch's current stream).
+    it = max(3, min(args.steps, 10))
+    fwd_ms, fwd_min = event_ms(fwd, it)
+    bwd_ms, bwd_min = event_ms(bwd, it)
+    delta_ms, _ = event_ms(lambda: bwd(binding.BWD_DELTA), it)
+    dq_ms, _ = event_ms(lambda: bwd(binding.BWD_DQ), it)
+    dkdv_ms, _ = event_ms(lambda: bwd(binding.BWD_DKDV), it)
+
+    f_fwd = W.fwd_flops(cfg, cu_np)
+    f_bwd = W.bwd_flops(cfg, cu_np)
+    value = (f_fwd + f_bwd) / (ms_per_step * 1e-3) / 1e12
+    fwd_tflops = f_fwd / (fwd_ms * 1e-3) / 1e12
+    bwd_tflops = f_bwd / (bwd_ms * 1e-3) / 1e12
+
+    # Roofline of the kernel that takes the most time.  Matrix FLOP each kernel executes per
+    # visible (query, key) pair and query head: forward 4D (S, PV); dK/dV kernel 8D (S, dP, dV,
+    # dK); dQ kernel 6D (S, dP recomputed, dQ), of which only the dQ product (2D) is not
+    # already counted in the dK/dV kernel.  Pairs are counted as L^2/2 per document.
+    pairs = f_fwd / (4.0 * cfg.D)   # = B * Hq * sum L^2 / 2
+    kernels = {
+        "attn_fwd_kernel": (fwd_ms, 4.0 * cfg.D * pairs),
+        "attn_bwd_dkdv_kernel": (dkdv_ms, 8.0 * cfg.D * pairs),
+        "attn_bwd_dq_kernel": (dq_ms, 6.0 * cfg.D * pairs),
+    }
+    dom = max(kernels, key=lambda n: kernels[n][0])
+    dom_ms, dom_flop = kernels[dom]
+    achieved = dom_flop / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "ms": dom_ms}
+
+    out = {
+        "metric": "causal attention fwd+bwd TFLOPS and % of bf16 MFMA peak, 1 MI355X, S=32K D=128",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "S": cfg.S, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D,
+                   "causal": cfg.causal, "packed_docs": None if cu_np is None else len(cu_np) - 1, "seed": cfg.seed},
+        "frac_of_peak": value / PEAK_BF16_TFLOPS,
+        "fwd": {"ms": fwd_ms, "ms_min": fwd_min, "tflops": fwd_tflops, "frac_of_peak": fwd_tflops / PEAK_BF16_TFLOPS},
+        "bwd": {"ms": bwd_ms, "ms_min": bwd_min, "tflops": bwd_tflops, "frac_of_peak": bwd_tflops / PEAK_BF16_TFLOPS,
+                "delta_ms": delta_ms, "dq_ms": dq_ms, "dkdv_ms": dkdv_ms},
+        "peak_tflops": PEAK_BF16_TFLOPS,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        prefix = min(args.cpu_prefix, cfg.S if cu_np is None else int(cu_np[1]))
+        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, dout, prefix, min(args.cpu_heads, cfg.Hq))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

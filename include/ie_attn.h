@@ -70,9 +70,9 @@ int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
                 float scale, int32_t causal, void* stream);
 
 /*
- * Bytes of device workspace ie_attn_bwd needs for this shape (delta [B,Hq,S] fp32, the
- * fp32 dq accumulator [B,S,Hq,D], fp32 dk/dv accumulators when Hq != Hkv).  Returns 0
- * for an invalid shape.  Pure host arithmetic; touches no device.
+ * Bytes of device workspace ie_attn_bwd needs for this shape (it holds delta [B,Hq,S]
+ * fp32 between the kernels of one call).  Returns 0 for an invalid shape.  Pure host
+ * arithmetic; touches no device.
  */
 size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs);
 
@@ -82,9 +82,8 @@ size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv
  * probabilities are recomputed from lse (Sec. 3.1), backward costs 2.5x the forward's
  * matrix work (cf. Sec. 4.3: backward is about twice as compute-intensive as forward).
  * `workspace` is caller-owned scratch of at least ie_attn_bwd_workspace_bytes(...) bytes,
- * 256-byte aligned; the library zero-fills what it needs on `stream`, its contents
- * after the call are unspecified.  dq is accumulated with fp32 atomics, so its last bits
- * may differ from run to run.
+ * 256-byte aligned; its contents after the call are unspecified.  Every output element
+ * has a single owner and a fixed summation order, so results are bitwise reproducible.
  */
 int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
                 const float* lse, void* dq, void* dk, void* dv,
@@ -92,6 +91,22 @@ int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
                 int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
                 float scale, int32_t causal,
                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same backward pass, restricted to some of its kernels, for profilers and benchmarks
+ * that time one kernel at a time.  `phases` is a bit mask: IE_BWD_DELTA (delta = rowsum(dO o O)
+ * into the workspace), IE_BWD_DQ (writes dq; needs delta in the workspace), IE_BWD_DKDV
+ * (writes dk and dv; needs delta).  Outputs of phases that are not selected are left
+ * untouched.  ie_attn_bwd(...) is ie_attn_bwd_phases(..., IE_BWD_ALL).  A mask of 0 or with
+ * other bits set is IE_ERR_UNSUPPORTED.
+ */
+enum { IE_BWD_DELTA = 1, IE_BWD_DQ = 2, IE_BWD_DKDV = 4, IE_BWD_ALL = 7 };
+int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                       const float* lse, void* dq, void* dk, void* dv,
+                       const int32_t* cu_seqlens, int32_t num_docs,
+                       int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
+                       float scale, int32_t causal,
+                       void* workspace, size_t workspace_bytes, int32_t phases, void* stream);
 
 /* Static text for a status code (never NULL). */
 const char* ie_attn_strerror(int code);

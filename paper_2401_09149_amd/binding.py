@@ -12,7 +12,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libie_attn.so")
 
-EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd", "ie_attn_strerror",
+EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases", "ie_attn_strerror",
            "ie_attn_last_hip_error")
 
 _lib = None
@@ -40,6 +40,8 @@ def load():
     lib.ie_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
     lib.ie_attn_bwd.argtypes = [vp] * 9 + [vp, i32, i64, i64, i32, i32, i32, f32, i32, vp, ctypes.c_size_t, vp]
     lib.ie_attn_bwd.restype = ctypes.c_int
+    lib.ie_attn_bwd_phases.argtypes = [vp] * 9 + [vp, i32, i64, i64, i32, i32, i32, f32, i32, vp, ctypes.c_size_t, i32, vp]
+    lib.ie_attn_bwd_phases.restype = ctypes.c_int
     lib.ie_attn_strerror.argtypes = [ctypes.c_int]
     lib.ie_attn_strerror.restype = ctypes.c_char_p
     lib.ie_attn_last_hip_error.argtypes = []
@@ -104,17 +106,25 @@ def ie_attn_fwd(q, k, v, o, lse, cu_seqlens, scale, causal, stream=None):
         _raise(rc)
 
 
+BWD_DELTA, BWD_DQ, BWD_DKDV, BWD_ALL = 1, 2, 4, 7
+
+
 def ie_attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, stream=None):
     """dq, dk, dv are overwritten; `workspace` is a uint8 GPU tensor of ie_attn_bwd_workspace_bytes(...)."""
+    ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, BWD_ALL, stream)
+
+
+def ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, phases, stream=None):
+    """Selected kernels of the backward pass (bit mask of BWD_DELTA, BWD_DQ, BWD_DKDV)."""
     B, S, Hq, Hkv, D = _shape(q, k)
     cu, nd = _docs(cu_seqlens)
     bf = torch.bfloat16
     ws = _ptr(workspace, torch.uint8, "workspace")
-    rc = load().ie_attn_bwd(_ptr(q, bf, "q"), _ptr(k, bf, "k"), _ptr(v, bf, "v"), _ptr(o, bf, "o"),
+    rc = load().ie_attn_bwd_phases(_ptr(q, bf, "q"), _ptr(k, bf, "k"), _ptr(v, bf, "v"), _ptr(o, bf, "o"),
                             _ptr(dout, bf, "dout"), _ptr(lse, torch.float32, "lse"), _ptr(dq, bf, "dq"),
                             _ptr(dk, bf, "dk"), _ptr(dv, bf, "dv"), cu, nd, B, S, Hq, Hkv, D, float(scale),
                             int(bool(causal)), ws, workspace.numel() if workspace is not None else 0,
-                            _stream(stream))
+                            int(phases), _stream(stream))
     if rc != 0:
         _raise(rc)
 

@@ -354,16 +354,16 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 }
 
 template <int D>
-static int launch_bwd_d(AttnParams p, hipStream_t st) {
+static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
   hipError_t e;
-  {  // delta
+  if (phases & 1) {  // delta
     constexpr int rows_per_block = (kThreads / (D / 8)) * 8;
     int64_t grid = ceil_div(p.S, rows_per_block) * p.B * p.Hq;
     if (grid >= ((int64_t)1 << 31)) return kErrShape;
     attn_bwd_delta_kernel<D><<<dim3((unsigned)grid), dim3(kThreads), 0, st>>>(p);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
   }
-  {  // dq
+  if (phases & 2) {  // dq
     constexpr int smem = 2 * 2 * 64 * D * 2;
     int rc = set_smem(attn_bwd_dq_kernel<D>, smem);
     if (rc) return rc;
@@ -374,7 +374,7 @@ static int launch_bwd_d(AttnParams p, hipStream_t st) {
     attn_bwd_dq_kernel<D><<<dim3((unsigned)grid), dim3(kThreads), smem, st>>>(p);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
   }
-  {  // dk, dv
+  if (phases & 4) {  // dk, dv
     constexpr int smem = 2 * (2 * 64 * D * 2 + 2 * 64 * 4);
     int rc = set_smem(attn_bwd_dkdv_kernel<D>, smem);
     if (rc) return rc;
@@ -388,8 +388,8 @@ static int launch_bwd_d(AttnParams p, hipStream_t st) {
   return 0;
 }
 
-int launch_bwd(AttnParams p, int D, hipStream_t st) {
-  return D == 64 ? launch_bwd_d<64>(p, st) : launch_bwd_d<128>(p, st);
+int launch_bwd(AttnParams p, int D, int phases, hipStream_t st) {
+  return D == 64 ? launch_bwd_d<64>(p, phases, st) : launch_bwd_d<128>(p, phases, st);
 }
 
 }  // namespace ie

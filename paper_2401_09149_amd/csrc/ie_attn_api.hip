@@ -82,9 +82,18 @@ int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
                 void* dq, void* dk, void* dv, const int32_t* cu_seqlens, int32_t num_docs, int64_t B, int64_t S,
                 int32_t Hq, int32_t Hkv, int32_t D, float scale, int32_t causal, void* workspace,
                 size_t workspace_bytes, void* stream) {
+  return ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale,
+                            causal, workspace, workspace_bytes, IE_BWD_ALL, stream);
+}
+
+int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                       const float* lse, void* dq, void* dk, void* dv, const int32_t* cu_seqlens,
+                       int32_t num_docs, int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale,
+                       int32_t causal, void* workspace, size_t workspace_bytes, int32_t phases, void* stream) {
   if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return IE_ERR_NULL;
   int rc = check_shape(cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal);
   if (rc) return rc;
+  if (phases <= 0 || (phases & ~IE_BWD_ALL) != 0) return IE_ERR_UNSUPPORTED;
   size_t need = ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < need) return IE_ERR_WORKSPACE;
   ie::AttnParams p = base_params(cu_seqlens, num_docs, B, S, Hq, Hkv, scale, causal);
@@ -99,7 +108,7 @@ int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
   p.dk = static_cast<__bf16*>(dk);
   p.dv = static_cast<__bf16*>(dv);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  return ie::launch_bwd(p, D, st);
+  return ie::launch_bwd(p, D, phases, st);
 }
 
 const char* ie_attn_strerror(int code) {

@@ -11,7 +11,8 @@ namespace ie {
 int hip_fail(hipError_t e);
 
 int launch_fwd(AttnParams p, int D, hipStream_t st);
-int launch_bwd(AttnParams p, int D, hipStream_t st);
+// phases: bit 0 delta, bit 1 dq, bit 2 dk/dv
+int launch_bwd(AttnParams p, int D, int phases, hipStream_t st);
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
