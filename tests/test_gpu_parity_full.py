@@ -1,0 +1,147 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot run whole heads of a 128K sequence in test time, so it computes sampled
+outputs one by one: blocks of query rows (o, lse, dq need only those rows) and blocks of
+key columns (dk, dv need the forward statistics of every later row of the document, which
+the oracle computes first).  Blocks are placed at the start, across tile boundaries, at
+document boundaries and at the end.  On top of that, identities that hold at any size are
+checked on the complete GPU outputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+from parity_util import TOL_GRAD_ABS, TOL_GRAD_REL, TOL_LSE, TOL_O, grad_errors
+
+pytestmark = pytest.mark.gpu
+
+
+def w64(t):
+    return np.ascontiguousarray(t.to("cpu", torch.float32).numpy().astype(np.float64))
+
+
+def run_full(cfg):
+    from paper_2401_09149_amd import binding, workloads as W
+    cu = W.make_cu_seqlens(cfg)
+    q, k, v, do = W.make_inputs(cfg)
+    dev = "cuda:0"
+    qd, kd, vd, dod = (x.to(dev) for x in (q, k, v, do))
+    cud = None if cu is None else torch.tensor(cu, dtype=torch.int32, device=dev)
+    o, lse = binding.attn_fwd(qd, kd, vd, cfg.scale, cfg.causal, cud)
+    dq, dk, dv = binding.attn_bwd(qd, kd, vd, o, dod, lse, cfg.scale, cfg.causal, cud)
+    torch.cuda.synchronize()
+    return cu, (q, k, v, do), (qd, kd, vd, dod), (o, lse, dq, dk, dv)
+
+
+def check_rows(oracle, cfg, cu, cpu_in, gpu_out, head, rows):
+    q, k, v, do = cpu_in
+    o, lse, dq, dk, dv = gpu_out
+    g = head // (cfg.Hq // cfg.Hkv)
+    q1, do1 = w64(q[:, :, head:head + 1]), w64(do[:, :, head:head + 1])
+    k1, v1 = w64(k[:, :, g:g + 1]), w64(v[:, :, g:g + 1])
+    for r0, r1 in rows:
+        print(f"  rows [{r0},{r1}) head {head}", flush=True)
+        ro, rlse = oracle.attn_fwd(q1, k1, v1, cfg.scale, cfg.causal, cu, rows=(r0, r1))
+        rdq = oracle.attn_bwd_dq(q1, k1, v1, ro, do1, rlse, cfg.scale, cfg.causal, cu, rows=(r0, r1))
+        go = w64(o[:, r0:r1, head:head + 1])
+        glse = w64(lse[:, head:head + 1, r0:r1])
+        gdq = w64(dq[:, r0:r1, head:head + 1])
+        eo = np.abs(go - ro[:, r0:r1]).max()
+        el = np.abs(glse - rlse[:, :, r0:r1]).max()
+        ea, er = grad_errors(gdq, rdq[:, r0:r1])
+        print(f"    o {eo:.2e} lse {el:.2e} dq abs {ea:.2e} rel {er:.2e}", flush=True)
+        assert eo <= TOL_O and el <= TOL_LSE and ea <= TOL_GRAD_ABS and er <= TOL_GRAD_REL
+
+
+def check_cols(oracle, cfg, cu, cpu_in, gpu_out, g, cols):
+    q, k, v, do = cpu_in
+    o, lse, dq, dk, dv = gpu_out
+    rep = cfg.Hq // cfg.Hkv
+    hs = slice(g * rep, (g + 1) * rep)
+    qg, dog = w64(q[:, :, hs]), w64(do[:, :, hs])
+    k1, v1 = w64(k[:, :, g:g + 1]), w64(v[:, :, g:g + 1])
+    for c0, c1 in cols:
+        need = oracle.rows_needed_for_cols(cfg.S, (c0, c1), cfg.causal, cu)
+        print(f"  cols [{c0},{c1}) kv head {g}: oracle forward over rows {need}", flush=True)
+        ro, rlse = oracle.attn_fwd(qg, k1, v1, cfg.scale, cfg.causal, cu, rows=need)
+        rdk, rdv = oracle.attn_bwd_dkdv(qg, k1, v1, ro, dog, rlse, cfg.scale, cfg.causal, cu, cols=(c0, c1))
+        for name, gt, rf in (("dk", dk, rdk), ("dv", dv, rdv)):
+            ea, er = grad_errors(w64(gt[:, c0:c1, g:g + 1]), rf[:, c0:c1])
+            print(f"    {name} abs {ea:.2e} rel {er:.2e}", flush=True)
+            assert ea <= TOL_GRAD_ABS and er <= TOL_GRAD_REL
+
+
+def check_identities(cfg, cu, gpu_in, gpu_out):
+    """Properties of the exact gradients that need no oracle (all sums in fp64 on the GPU):
+    <q,dq> over a group = <k,dk>; <v,dv> = <o,dO> over the group; sum_j dk_j = 0 per document."""
+    qd, kd, vd, dod = gpu_in
+    o, lse, dq, dk, dv = gpu_out
+    assert all(bool(torch.isfinite(t.float()).all()) for t in gpu_out)
+    rep = cfg.Hq // cfg.Hkv
+    f = lambda t: t.to(torch.float64)
+    for g in range(cfg.Hkv):
+        hs = slice(g * rep, (g + 1) * rep)
+        qdq = float((f(qd[:, :, hs]) * f(dq[:, :, hs])).sum())
+        kdk = float((f(kd[:, :, g]) * f(dk[:, :, g])).sum())
+        vdv = float((f(vd[:, :, g]) * f(dv[:, :, g])).sum())
+        odo = float((f(o[:, :, hs]) * f(dod[:, :, hs])).sum())
+        # scale for "small": the norm of the summands, since the sums themselves cancel heavily
+        nq = float((f(qd[:, :, hs]) * f(dq[:, :, hs])).abs().sum())
+        nv = float((f(vd[:, :, g]) * f(dv[:, :, g])).abs().sum())
+        print(f"  kv head {g}: <q,dq>={qdq:.4e} <k,dk>={kdk:.4e} (|.|={nq:.3e})  <v,dv>={vdv:.4e} <o,dO>={odo:.4e} (|.|={nv:.3e})", flush=True)
+        assert abs(qdq - kdk) <= 2e-3 * nq
+        assert abs(vdv - odo) <= 2e-3 * nv
+    bounds = [(0, cfg.S)] if cu is None else [(int(a), int(e)) for a, e in zip(cu[:-1], cu[1:]) if e > a]
+    for a, e in bounds[:4] + bounds[-2:]:
+        s = f(dk[:, a:e]).sum(dim=1)
+        n = f(dk[:, a:e]).abs().sum(dim=1)
+        assert float((s.abs() / n.clamp_min(1e-30)).max()) <= 5e-3
+
+
+def test_config1_s32k_h32(oracle):
+    from paper_2401_09149_amd import workloads as W
+    cfg = W.CONFIGS[1]
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    S = cfg.S
+    check_rows(oracle, cfg, cu, cpu_in, gpu_out, 0, [(0, 40), (8180, 8200), (S - 33, S)])
+    check_rows(oracle, cfg, cu, cpu_in, gpu_out, 31, [(16370, 16400)])
+    check_cols(oracle, cfg, cu, cpu_in, gpu_out, 5, [(S - 200, S - 150), (20470, 20490)])
+    check_identities(cfg, cu, gpu_in, gpu_out)
+
+
+def test_config2_s128k_h8(oracle):
+    from paper_2401_09149_amd import workloads as W
+    cfg = W.CONFIGS[2]
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    S = cfg.S
+    check_rows(oracle, cfg, cu, cpu_in, gpu_out, 3, [(0, 20), (65530, 65545), (S - 20, S)])
+    check_cols(oracle, cfg, cu, cpu_in, gpu_out, 7, [(S - 130, S - 100), (110580, 110600)])
+    check_identities(cfg, cu, gpu_in, gpu_out)
+
+
+def test_config3_gqa_s64k(oracle):
+    from paper_2401_09149_amd import workloads as W
+    cfg = W.CONFIGS[3]
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    S = cfg.S
+    check_rows(oracle, cfg, cu, cpu_in, gpu_out, 0, [(0, 20), (S - 20, S)])
+    check_rows(oracle, cfg, cu, cpu_in, gpu_out, 7, [(32760, 32780)])
+    check_cols(oracle, cfg, cu, cpu_in, gpu_out, 0, [(S - 70, S - 40), (60150, 60170)])
+    check_identities(cfg, cu, gpu_in, gpu_out)
+
+
+def test_config4_packed_256k(oracle):
+    from paper_2401_09149_amd import workloads as W
+    cfg = W.CONFIGS[4]
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    lens = np.diff(cu)
+    # rows straddling a document boundary, the start and end of the longest document, and the tail
+    longest = int(np.argmax(lens))
+    a, e = int(cu[longest]), int(cu[longest + 1])
+    b1 = int(cu[3])
+    check_rows(oracle, cfg, cu, cpu_in, gpu_out, 1, [(b1 - 10, b1 + 10), (a, a + 12), (e - 15, e), (cfg.S - 10, cfg.S)])
+    # columns: a whole short document, and the end of the longest one
+    short = int(np.argmin(np.where(lens > 0, lens, 1 << 30)))
+    sa, se = int(cu[short]), int(cu[short + 1])
+    check_cols(oracle, cfg, cu, cpu_in, gpu_out, 2, [(sa, min(se, sa + 64)), (e - 300, e - 270), (a + 130, a + 140) if e - a < 20000 else (e - 9000, e - 8990)])
+    check_identities(cfg, cu, gpu_in, gpu_out)
