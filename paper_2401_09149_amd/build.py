@@ -8,9 +8,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libie_attn.so")
 SOURCES = ["ie_attn_api.hip", "attn_fwd.hip", "attn_bwd.hip"]
+# -fno-honor-nans: the kernels never produce NaN from finite inputs (masked scores are -inf and only ever
+# meet finite references), and without it every max is preceded by a canonicalising self-max.
 # Packed fp32 VALU forms are switched off for all device code (known to misbehave on the test machines).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+         "-packed-fp32-ops", "-fno-honor-nans", "-Wall", "-Wno-unused-command-line-argument"]
 
 
 def _compile(src, extra):

@@ -12,6 +12,8 @@
 // (one column per lane, rows over registers) with the NEXT contraction index on the
 // rows, so they feed the following MFMA from registers; the transposed operands
 // (K^T, dO^T, Q^T) are gathered from row-major LDS tiles with transpose loads.
+#include <type_traits>
+
 #include "attn_common.hpp"
 #include "launch.hpp"
 
@@ -20,7 +22,9 @@ namespace ie {
 // ---- delta = rowsum(dO o O) ------------------------------------------------------------
 // One (batch, token, head) row of D bf16 per group of D/8 lanes; rows are walked so that
 // consecutive groups take consecutive tokens of one head, which makes the [B,Hq,S]
-// writes contiguous while every read is a full row (D*2 contiguous bytes).
+// writes contiguous while every read is a full row (D*2 contiguous bytes).  The same pass
+// stores lse * log2(e) next to delta, so that the main kernels can exponentiate with exp2
+// without a per-element rescale.
 template <int D>
 __global__ __launch_bounds__(kThreads) void attn_bwd_delta_kernel(AttnParams p) {
   constexpr int LPR = D / 8;               // lanes per row
@@ -45,16 +49,24 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_delta_kernel(AttnParams p) 
     }
 #pragma unroll
     for (int s = LPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s, 64);
-    if (sub == 0 && i < p.S) p.delta[hh * p.S + i] = acc;
+    if (sub == 0 && i < p.S) {
+      p.delta[hh * p.S + i] = acc;
+      p.lse2[hh * p.S + i] = p.lse[hh * p.S + i] * kLog2e;
+    }
   }
 }
 
 // ---- dQ ----------------------------------------------------------------------------------
+// Same skeleton as the forward kernel: 128 query rows per workgroup (32 per wave, Q and dO
+// fragments in registers), 64-key K/V tiles double-buffered in LDS by asynchronous copies,
+// each consumed as two 32-key blocks.
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) {
   constexpr int BM = 128, BN = 64;
   constexpr int NKS = D / 16, NDB = D / 32;
   constexpr int TILE_BYTES = BN * D * 2;
+  constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+  constexpr int ROW_BYTES = D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
@@ -68,16 +80,27 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   const int64_t q_end = (q0 + BM < tc.doc_end) ? q0 + BM : tc.doc_end;
   const int64_t k_begin = tc.doc_begin;
   const int64_t k_end = p.causal ? q_end : tc.doc_end;
-  const int nkt = (int)((k_end - k_begin + BN - 1) / BN);
+  const int nk = (int)(k_end - k_begin);
+  const int nkt = (nk + BN - 1) / BN;
+  const int nfull = nk / BN;
 
-  const int64_t q_stride = (int64_t)p.Hq * D, kv_stride = (int64_t)p.Hkv * D;
+  const int64_t q_stride = (int64_t)p.Hq * D;
+  const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
   const int64_t qhead = ((int64_t)tc.b * p.S * p.Hq + tc.h) * D;
-  const __bf16* kbase = p.k + ((int64_t)tc.b * p.S * p.Hkv + g) * D;
-  const __bf16* vbase = p.v + ((int64_t)tc.b * p.S * p.Hkv + g) * D;
+  const char* kbase = reinterpret_cast<const char*>(p.k + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D);
+  const char* vbase = reinterpret_cast<const char*>(p.v + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D);
+  const int64_t tile_pitch = BN * kv_pitch;
+
+  const uint32_t lds0 = lds_address(smem);
+  AsyncTile<D> ld;
+  ld.init(tid, kv_pitch);
+  ld.load(lds0, kbase, nk);
+  ld.load(lds0 + TILE_BYTES, vbase, nk);
 
   int64_t row = q0 + wv * 32 + n;
   const bool row_ok = row < q_end;
   if (!row_ok) row = q_end - 1;
+  const int row_rel = (int)(row - k_begin);
 
   bf16x8 qf[NKS], dof[NKS];
 #pragma unroll
@@ -86,27 +109,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
     dof[ks] = *reinterpret_cast<const bf16x8*>(p.dout + qhead + row * q_stride + ks * 16 + h * 8);
   }
   const int64_t stat = ((int64_t)tc.b * p.Hq + tc.h) * p.S + row;
-  const float lse2 = p.lse[stat] * kLog2e;
+  const float lse2 = p.lse2[stat];
   const float delta = p.delta[stat];
 
-  int nat_off[2][NKS];
+  const char* nat_ptr[NKS];  // row n of a tile, chunk 2ks + h (A operand: K or V rows)
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) nat_off[j][ks] = tile_off<D>(32 * j + n, 2 * ks + h);
-  int tr0[NDB], tr8[NDB];
+  for (int ks = 0; ks < NKS; ++ks) nat_ptr[ks] = smem + tile_off<D>(n, 2 * ks + h);
+  const char* tr_ptr0[NDB];  // transpose loads on the K tile
+  const char* tr_ptr8[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db) {
-    tr0[db] = tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
-    tr8[db] = tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    tr_ptr0[db] = smem + tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    tr_ptr8[db] = smem + tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
   }
-
-  TileRegs<BN, D> kr, vr;
-  tile_load<BN, D>(kr, kbase, kv_stride, k_begin, k_end - 1, tid);
-  tile_load<BN, D>(vr, vbase, kv_stride, k_begin, k_end - 1, tid);
-  tile_store<BN, D>(kr, smem, tid);
-  tile_store<BN, D>(vr, smem + TILE_BYTES, tid);
-  __syncthreads();
 
   const float c = p.scale_log2;
   f32x16 acc[NDB];
@@ -115,61 +130,80 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-  const int64_t wave_row_min = q0 + wv * 32;
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int64_t kb = k_begin + (int64_t)kt * BN;
-    const char* ks_lds = smem + (kt & 1) * 2 * TILE_BYTES;
-    const char* vs_lds = ks_lds + TILE_BYTES;
-    const bool more = kt + 1 < nkt;
-    if (more) {
-      tile_load<BN, D>(kr, kbase, kv_stride, kb + BN, k_end - 1, tid);
-      tile_load<BN, D>(vr, vbase, kv_stride, kb + BN, k_end - 1, tid);
+  const int wave_row_min = (int)(q0 - k_begin) + wv * 32;
+
+  auto tile_step = [&](const int kt, const int stage, auto full_next) {
+    const int kb = kt * BN;
+    const uint32_t next_lds = lds0 + (STAGE_BYTES - stage);
+    if (full_next) {
+      ld.load_full(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch);
+      ld.load_full(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch);
+    } else if (kt + 1 < nkt) {
+      ld.load(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch, nk - kb - BN);
+      ld.load(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch, nk - kb - BN);
     }
-    const bool need_mask = (p.causal && kb + BN - 1 > wave_row_min) || (kb + BN > k_end);
-    const int64_t lim = p.causal ? (row < k_end - 1 ? row : k_end - 1) : k_end - 1;
+    const bool need_mask = (p.causal && kb + BN - 1 > wave_row_min) || (kb + BN > nk);
+    const int lim = (p.causal ? row_rel : nk - 1) - kb - 4 * h;
 
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
+      const int blk = stage + 32 * j * ROW_BYTES;
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) s = mfma32(lds_read8(ks_lds, nat_off[j][ks]), qf[ks], s);
+      for (int ks = 0; ks < NKS; ++ks) s = mfma32(lds_read8(nat_ptr[ks], blk), qf[ks], s);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) dp = mfma32(lds_read8(vs_lds, nat_off[j][ks]), dof[ks], dp);
+      for (int ks = 0; ks < NKS; ++ks) dp = mfma32(lds_read8(nat_ptr[ks], blk + TILE_BYTES), dof[ks], dp);
+      // K^T fragments for the dQ product: requested before the elementwise work
+      bf16x8 ktf[2][NDB];
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const int off = blk + 16 * sblk * ROW_BYTES;
+          ktf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off), lds_read_tr4(tr_ptr8[db] + off));
+        }
       if (need_mask) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int64_t key = kb + 32 * j + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (key > lim) s[r] = -INFINITY;
-        }
+        for (int r = 0; r < 16; ++r)
+          if (32 * j + 8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
       }
       bf16x8 dsf[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
-        dsf[r >> 3][r & 7] = (__bf16)(pr * (dp[r] - delta));
+      for (int sblk = 0; sblk < 2; ++sblk) {
+        bf16x2 pr[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int r = 8 * sblk + 2 * t;
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], c, -lse2));
+          pr[t] = pack_bf16(p0 * (dp[r] - delta), p1 * (dp[r + 1] - delta));
+        }
+        dsf[sblk] = cat_pairs(pr[0], pr[1], pr[2], pr[3]);
       }
       // dQ^T += K^T dS^T over this block's 32 keys
 #pragma unroll
-      for (int sblk = 0; sblk < 2; ++sblk) {
-        const int rowbytes = (32 * j + 16 * sblk) * (D * 2);
+      for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          bf16x4 lo = lds_read_tr4(ks_lds + rowbytes + tr0[db]);
-          bf16x4 hi = lds_read_tr4(ks_lds + rowbytes + tr8[db]);
-          acc[db] = mfma32(cat4(lo, hi), dsf[sblk], acc[db]);
-        }
-      }
+        for (int db = 0; db < NDB; ++db) acc[db] = mfma32(ktf[sblk][db], dsf[sblk], acc[db]);
     }
-
-    if (more) {
-      char* nk = smem + ((kt + 1) & 1) * 2 * TILE_BYTES;
-      tile_store<BN, D>(kr, nk, tid);
-      tile_store<BN, D>(vr, nk + TILE_BYTES, tid);
-    }
+    async_wait_all();
     __syncthreads();
+  };
+
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) { consume(qf[ks]); consume(dof[ks]); }
+  consume(lse2);
+  consume(delta);
+  async_wait_all();
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 2 < nfull; kt += 2) {
+    tile_step(kt, 0, std::true_type{});
+    tile_step(kt + 1, STAGE_BYTES, std::true_type{});
   }
+  for (; kt < nkt; ++kt) tile_step(kt, (kt & 1) * STAGE_BYTES, std::false_type{});
 
   if (row_ok) {
     __bf16* drow = p.dq + qhead + row * q_stride;
@@ -186,13 +220,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
 }
 
 // ---- dK, dV ------------------------------------------------------------------------------
+// One workgroup per (batch, kv head, 128 keys); wave w owns keys 32w..32w+31 and keeps their
+// K and V fragments and the dK^T / dV^T accumulators in registers for the whole kernel.
+// Query tiles of 64 rows (Q, dO, lse*log2e, delta) stream through a ring of LDS stages
+// filled by asynchronous copies; all query heads of the kv head's group pass through the
+// same accumulators, which is the GQA reduction.
+template <int D>
+struct DkdvCfg {
+  static constexpr int BK = 128, BQ = 64;
+  static constexpr int TILE_BYTES = BQ * D * 2;
+  static constexpr int STAT_BYTES = 2 * BQ * 4;                   // lse*log2e [64], delta [64]
+  static constexpr int STAGE_BYTES = 2 * TILE_BYTES + STAT_BYTES; // Q, dO, stats
+  static constexpr int STAGES = 2;
+  static constexpr int SMEM_BYTES = STAGES * STAGE_BYTES;
+};
+
 template <int D>
 __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p) {
-  constexpr int BK = 128;  // keys per workgroup, 32 per wavefront
-  constexpr int BQ = 64;   // query rows per loop step
+  using C = DkdvCfg<D>;
+  constexpr int BK = C::BK, BQ = C::BQ;
   constexpr int NKS = D / 16, NDB = D / 32;
-  constexpr int TILE_BYTES = BQ * D * 2;
-  constexpr int STAGE_BYTES = 2 * TILE_BYTES + 2 * BQ * 4;  // Q, dO, lse*log2e, delta
+  constexpr int TILE_BYTES = C::TILE_BYTES, STAGE_BYTES = C::STAGE_BYTES;
+  constexpr int ROW_BYTES = D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
@@ -205,16 +254,48 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   const int group = p.Hq / p.Hkv;
   const int64_t k0 = tc.t0;
   const int64_t q_begin = p.causal ? k0 : tc.doc_begin;
-  const int64_t q_end = tc.doc_end;
-  const int nqt = (int)((q_end - q_begin + BQ - 1) / BQ);
+  const int nq = (int)(tc.doc_end - q_begin);  // query rows that can see this key tile
+  const int nqt = (nq + BQ - 1) / BQ;
+  const int total = nqt * group;               // loop steps: query heads of the group x query tiles
 
-  const int64_t q_stride = (int64_t)p.Hq * D, kv_stride = (int64_t)p.Hkv * D;
+  const int64_t q_pitch = (int64_t)p.Hq * D * 2;  // bytes between consecutive tokens of one query head
+  const int64_t kv_stride = (int64_t)p.Hkv * D;
   const int64_t kvhead = ((int64_t)tc.b * p.S * p.Hkv + g) * D;
+
+  const uint32_t lds0 = lds_address(smem);
+  AsyncTile<D> ld;
+  ld.init(tid, q_pitch);
+  const int wave_u = ld.wave;
+
+  // Asynchronous copy of step `st` (query head, query tile) into stage `slot`.
+  auto issue_step = [&](const int st, const int slot) {
+    const int hq = g * group + st / nqt;
+    const int i0 = (st % nqt) * BQ;  // first row of the tile, relative to q_begin
+    const int rows = nq - i0;        // valid rows (>= 1)
+    const int64_t tok = (int64_t)tc.b * p.S + q_begin + i0;
+    const char* qg = reinterpret_cast<const char*>(p.q + (tok * p.Hq + hq) * D);
+    const char* dog = reinterpret_cast<const char*>(p.dout + (tok * p.Hq + hq) * D);
+    const uint32_t base = lds0 + slot * STAGE_BYTES;
+    ld.load(base, qg, rows);
+    ld.load(base + TILE_BYTES, dog, rows);
+    // statistics: wave 0 copies lse*log2e, wave 1 copies delta (one dword per lane = one row)
+    if (wave_u < 2) {
+      int r = lane < rows ? lane : rows - 1;
+      const int64_t idx = ((int64_t)tc.b * p.Hq + hq) * p.S + q_begin + i0;
+      const float* src = (wave_u == 0 ? p.lse2 : p.delta) + idx;
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                   :
+                   : "v"((uint32_t)r * 4u), "s"(src), "s"(base + 2 * TILE_BYTES + wave_u * BQ * 4)
+                   : "memory");
+    }
+  };
+  issue_step(0, 0);
 
   // This lane's key (column of S); clamped copies are computed but never written.
   int64_t key = k0 + wv * 32 + n;
   const bool key_ok = key < tc.doc_end;
   const int64_t key_ld = key_ok ? key : tc.doc_end - 1;
+  const int key_rel = (int)(key - q_begin);  // position of the key among the rows that see the tile
   bf16x8 kf[NKS], vf[NKS];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
@@ -222,17 +303,17 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     vf[ks] = *reinterpret_cast<const bf16x8*>(p.v + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
   }
 
-  int nat_off[2][NKS];
+  const char* nat_ptr[NKS];  // row n of a tile, chunk 2ks + h (A operand: Q or dO rows)
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) nat_off[rb][ks] = tile_off<D>(32 * rb + n, 2 * ks + h);
-  int tr0[NDB], tr8[NDB];
+  for (int ks = 0; ks < NKS; ++ks) nat_ptr[ks] = smem + tile_off<D>(n, 2 * ks + h);
+  const char* tr_ptr0[NDB];
+  const char* tr_ptr8[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db) {
-    tr0[db] = tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
-    tr8[db] = tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    tr_ptr0[db] = smem + tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    tr_ptr8[db] = smem + tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
   }
+  const char* stat_ptr = smem + 2 * TILE_BYTES + 16 * h;  // this half-wave's 4-row groups of the statistics
 
   f32x16 dkacc[NDB], dvacc[NDB];
 #pragma unroll
@@ -241,98 +322,85 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
 
   const float c = p.scale_log2;
-  const int total = nqt * group;  // loop steps: query heads of the group x query tiles
 
-  TileRegs<BQ, D> qr, dor;
-  float stat_reg = 0.f;  // threads 0..63: lse * log2e of row tid; threads 64..127: delta of row tid-64
-
-  auto load_step = [&](int step) {
-    const int hq = g * group + step / nqt;
-    const int64_t i0 = q_begin + (int64_t)(step % nqt) * BQ;
-    const int64_t qhead = ((int64_t)tc.b * p.S * p.Hq + hq) * D;
-    tile_load<BQ, D>(qr, p.q + qhead, q_stride, i0, q_end - 1, tid);
-    tile_load<BQ, D>(dor, p.dout + qhead, q_stride, i0, q_end - 1, tid);
-    if (tid < 2 * BQ) {
-      int64_t i = i0 + (tid & (BQ - 1));
-      i = i < q_end ? i : q_end - 1;
-      const int64_t idx = ((int64_t)tc.b * p.Hq + hq) * p.S + i;
-      stat_reg = tid < BQ ? p.lse[idx] * kLog2e : p.delta[idx];
-    }
-  };
-  auto store_step = [&](char* stage) {
-    tile_store<BQ, D>(qr, stage, tid);
-    tile_store<BQ, D>(dor, stage + TILE_BYTES, tid);
-    if (tid < 2 * BQ) reinterpret_cast<float*>(stage + 2 * TILE_BYTES)[tid] = stat_reg;
-  };
-
-  load_step(0);
-  store_step(smem);
-  __syncthreads();
-
-  for (int step = 0; step < total; ++step) {
-    const char* st = smem + (step & 1) * STAGE_BYTES;
-    const char* q_lds = st;
-    const char* do_lds = st + TILE_BYTES;
-    const float* lse_lds = reinterpret_cast<const float*>(st + 2 * TILE_BYTES);
-    const float* delta_lds = lse_lds + BQ;
-    const bool more = step + 1 < total;
-    if (more) load_step(step + 1);
-
-    const int64_t i0 = q_begin + (int64_t)(step % nqt) * BQ;
+  auto step_fn = [&](const int st, const int stage) {
+    if (st + 1 < total) issue_step(st + 1, (STAGE_BYTES - stage) / STAGE_BYTES);
+    const int i0 = (st % nqt) * BQ;
     // Mask when a key of this wave can exceed a row of the tile (causal) or rows run past the document.
-    const bool need_mask = (p.causal && k0 + wv * 32 + 31 > i0) || (i0 + BQ > q_end);
+    const bool need_mask = (p.causal && wv * 32 + 31 > i0) || (i0 + BQ > nq);
 
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
+      const int blk = stage + 32 * rb * ROW_BYTES;
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) s = mfma32(lds_read8(q_lds, nat_off[rb][ks]), kf[ks], s);
+      for (int ks = 0; ks < NKS; ++ks) s = mfma32(lds_read8(nat_ptr[ks], blk), kf[ks], s);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) dp = mfma32(lds_read8(do_lds, nat_off[rb][ks]), vf[ks], dp);
+      for (int ks = 0; ks < NKS; ++ks) dp = mfma32(lds_read8(nat_ptr[ks], blk + TILE_BYTES), vf[ks], dp);
+      // transposed operands of the two accumulating products, requested before the elementwise work
+      bf16x8 dotf[2][NDB], qtf[2][NDB];
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const int off = blk + 16 * sblk * ROW_BYTES;
+          dotf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off + TILE_BYTES), lds_read_tr4(tr_ptr8[db] + off + TILE_BYTES));
+          qtf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off), lds_read_tr4(tr_ptr8[db] + off));
+        }
       if (need_mask) {
+        const int lim_c = p.causal ? key_rel - i0 - 32 * rb - 4 * h : -(1 << 30);  // rows below this see no key of the lane
+        const int lim_e = nq - i0 - 32 * rb - 4 * h;                                // rows from here on do not exist
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          int64_t i = i0 + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-          if ((p.causal && key > i) || i >= q_end) s[r] = -INFINITY;
+          const int ri = 8 * (r >> 2) + (r & 3);
+          if (ri < lim_c || ri >= lim_e) s[r] = -INFINITY;
         }
       }
       bf16x8 pf[2], dsf[2];
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int ri = 32 * rb + 8 * q4 + 4 * h;
-        f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_lds + ri);
-        f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_lds + ri);
+      for (int sblk = 0; sblk < 2; ++sblk) {
+        bf16x2 pp[4], dd[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int r = 4 * q4 + t;
-          float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[t]));
-          pf[r >> 3][r & 7] = (__bf16)pr;
-          dsf[r >> 3][r & 7] = (__bf16)(pr * (dp[r] - d4[t]));
+        for (int half = 0; half < 2; ++half) {
+          const int q4 = 2 * sblk + half;
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat_ptr + stage + (32 * rb + 8 * q4) * 4);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat_ptr + stage + (BQ + 32 * rb + 8 * q4) * 4);
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2) {
+            const int r = 4 * q4 + 2 * t2;
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[2 * t2]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], c, -l4[2 * t2 + 1]));
+            pp[2 * half + t2] = pack_bf16(p0, p1);
+            dd[2 * half + t2] = pack_bf16(p0 * (dp[r] - d4[2 * t2]), p1 * (dp[r + 1] - d4[2 * t2 + 1]));
+          }
         }
+        pf[sblk] = cat_pairs(pp[0], pp[1], pp[2], pp[3]);
+        dsf[sblk] = cat_pairs(dd[0], dd[1], dd[2], dd[3]);
       }
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk) {
-        const int rowbytes = (32 * rb + 16 * sblk) * (D * 2);
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          bf16x4 lo = lds_read_tr4(do_lds + rowbytes + tr0[db]);
-          bf16x4 hi = lds_read_tr4(do_lds + rowbytes + tr8[db]);
-          dvacc[db] = mfma32(cat4(lo, hi), pf[sblk], dvacc[db]);
-        }
+        for (int db = 0; db < NDB; ++db) dvacc[db] = mfma32(dotf[sblk][db], pf[sblk], dvacc[db]);
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          bf16x4 lo = lds_read_tr4(q_lds + rowbytes + tr0[db]);
-          bf16x4 hi = lds_read_tr4(q_lds + rowbytes + tr8[db]);
-          dkacc[db] = mfma32(cat4(lo, hi), dsf[sblk], dkacc[db]);
-        }
+        for (int db = 0; db < NDB; ++db) dkacc[db] = mfma32(qtf[sblk][db], dsf[sblk], dkacc[db]);
       }
     }
-
-    if (more) store_step(smem + ((step + 1) & 1) * STAGE_BYTES);
+    async_wait_all();
     __syncthreads();
+  };
+
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) { consume(kf[ks]); consume(vf[ks]); }
+  async_wait_all();
+  __syncthreads();
+  int st = 0;
+  for (; st + 1 < total; st += 2) {
+    step_fn(st, 0);
+    step_fn(st + 1, STAGE_BYTES);
   }
+  if (st < total) step_fn(st, 0);
 
   if (key_ok) {
     __bf16* dkrow = p.dk + kvhead + key * kv_stride;
@@ -375,7 +443,7 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
   }
   if (phases & 4) {  // dk, dv
-    constexpr int smem = 2 * (2 * 64 * D * 2 + 2 * 64 * 4);
+    constexpr int smem = DkdvCfg<D>::SMEM_BYTES;
     int rc = set_smem(attn_bwd_dkdv_kernel<D>, smem);
     if (rc) return rc;
     int64_t tiles = tiles_per_head(p.S, 128, p.cu, p.num_docs);

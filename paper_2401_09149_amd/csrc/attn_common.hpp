@@ -38,7 +38,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 struct AttnParams {
   const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* dout;
   __bf16* o_out; float* lse_out;
-  const float* lse; float* delta;
+  const float* lse; float* delta; float* lse2;  // lse2 = lse * log2(e), written by the delta kernel
   __bf16* dq; __bf16* dk; __bf16* dv;
   const int32_t* cu; int32_t num_docs;
   int64_t B, S;
@@ -145,6 +145,104 @@ __device__ __forceinline__ void tile_store(const TileRegs<ROWS, D>& t, char* lds
     int r = c / (D / 8), ch = c % (D / 8);
     *reinterpret_cast<u32x4*>(lds + tile_off<D>(r, ch)) = t.r[i];
   }
+}
+
+// ---- global -> LDS tile copies without a register stop -----------------------------------
+// global_load_lds_dwordx4 writes lane L's 16 bytes to LDS at M0 + 16 L, so one wave
+// instruction fills 1 KiB = 64 consecutive chunk positions of the tile.  The swizzle is
+// applied on the global side: the lane that owns chunk POSITION pc of row r fetches the
+// LOGICAL chunk pc ^ swz(r) of that row (still inside the row's contiguous D*2 bytes).
+// A 64-row tile takes 64*D*2/1024 wave instructions, dealt round-robin to the 4 waves.
+//
+// The instruction is issued from inline assembly on purpose: written as a builtin, the
+// compiler cannot tell the LDS stage being filled from the stage being read and drains
+// every outstanding copy (s_waitcnt vmcnt(0)) in front of the first LDS read that follows,
+// which serialises the prefetch with the arithmetic.  The price is that the kernel itself
+// must call async_wait_all() before the barrier that publishes a filled stage.  M0 is written
+// without telling the compiler (it is a reserved register that cannot be listed as a clobber);
+// nothing else in these kernels uses M0.
+__device__ __forceinline__ void async_copy16(uint32_t voffset, const char* sbase, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voffset), "s"(sbase), "s"(lds_addr)
+               : "memory");
+}
+__device__ __forceinline__ void async_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Makes the compiler treat `x` as consumed here, so that the wait for the global load that
+// produces it is placed here and not at its first real use.  Needed before a pipelined loop:
+// a wait left inside the loop body would, from the second trip on, drain the asynchronous
+// copies issued at the top of the trip instead (the hardware counter is shared).
+template <typename T>
+__device__ __forceinline__ void consume(const T& x) {
+  asm volatile("" ::"v"(x));
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void* p) {  // LDS byte address of a pointer into shared memory
+  return (uint32_t)(uintptr_t)p;
+}
+
+template <int D>
+struct AsyncTile {
+  static constexpr int CPR = D / 8;          // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;       // rows per wave instruction
+  static constexpr int NI = 64 / RPI / 4;    // instructions per wave per tile
+  int row0;             // row this lane fetches in instruction 0 (instruction i adds 4 * RPI * i)
+  uint32_t chunk_byte;  // byte offset of its logical chunk inside the row
+  uint32_t voff;        // row0 * pitch + chunk_byte
+  uint32_t pitch;       // bytes between consecutive rows (< 2^24)
+  int wave;             // wave index, uniform
+
+  __device__ __forceinline__ void init(int tid, int64_t pitch_bytes) {
+    const int lane = tid & 63;
+    wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    row0 = wave * RPI + lane / CPR;
+    chunk_byte = ((lane % CPR) ^ swz<D>(row0)) << 4;  // swz depends on row & 15 only; 4*RPI*i is a multiple of 16
+    pitch = (uint32_t)pitch_bytes;
+    voff = (uint32_t)row0 * pitch + chunk_byte;
+  }
+
+  // Copies 64 full rows starting at `g` (wave-uniform) into the LDS tile at byte address `lds`.
+  __device__ __forceinline__ void load_full(uint32_t lds, const char* g) const {
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      async_copy16(voff, g + (uint64_t)(4 * RPI * i) * pitch, lds + (i * 4 + wave) * 1024);
+  }
+  // Same when only rows [0, rows_valid) exist: later rows repeat row rows_valid-1 so that no
+  // load leaves the tensor (their values are masked by the caller).  1 <= rows_valid <= 64.
+  __device__ __forceinline__ void load_partial(uint32_t lds, const char* g, int rows_valid) const {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      int r = row0 + 4 * RPI * i;
+      r = r < rows_valid ? r : rows_valid - 1;
+      async_copy16((uint32_t)r * pitch + chunk_byte, g, lds + (i * 4 + wave) * 1024);
+    }
+  }
+  __device__ __forceinline__ void load(uint32_t lds, const char* g, int rows_valid) const {
+    if (rows_valid >= 64) load_full(lds, g);
+    else load_partial(lds, g, rows_valid);
+  }
+};
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Rounds two floats to bf16 (nearest even) into one register.
+__device__ __forceinline__ bf16x2 pack_bf16(float a, float b) {
+  bf16x2 r;
+  r[0] = (__bf16)a;
+  r[1] = (__bf16)b;
+  return r;
+}
+// acc + p[0] + p[1] in fp32 (v_dot2c_f32_bf16 against a pair of ones).
+__device__ __forceinline__ float add_pair(bf16x2 p, float acc) {
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  return __builtin_amdgcn_fdot2_f32_bf16(p, ones, acc, false);
+}
+// Four bf16 pairs -> one 8-element MFMA operand.
+__device__ __forceinline__ bf16x8 cat_pairs(bf16x2 a, bf16x2 b, bf16x2 c, bf16x2 d) {
+  u32x4 w = {__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, c),
+             __builtin_bit_cast(uint32_t, d)};
+  return __builtin_bit_cast(bf16x8, w);
 }
 
 // ---- workgroup -> (batch, head, document, tile) ----------------------------------------

@@ -8,6 +8,8 @@
 // one half-wave swap, and the exponentiated scores are already in the B-operand layout
 // of the second product O^T = V^T P^T, whose A operand (V^T) is gathered from the
 // row-major V tile by LDS transpose loads.
+#include <type_traits>
+
 #include "attn_common.hpp"
 #include "launch.hpp"
 
@@ -19,12 +21,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
   constexpr int NKS = D / 16;  // k-steps of the QK^T product
   constexpr int NDB = D / 32;  // 32-wide blocks of the head dimension in O^T
   constexpr int TILE_BYTES = BN * D * 2;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  // stage s: K at smem + s * 2 * TILE_BYTES, V right after it
+  constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K tile, then V tile
+  constexpr int ROW_BYTES = D * 2;
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // 2 stages
   __shared__ int scratch[8];
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int n = lane & 31, h = lane >> 5;
+  const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
 
   TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch);
   if (!tc.valid) return;
@@ -33,17 +36,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
   const int64_t q_end = (q0 + BM < tc.doc_end) ? q0 + BM : tc.doc_end;  // one past the tile's last row
   const int64_t k_begin = tc.doc_begin;
   const int64_t k_end = p.causal ? q_end : tc.doc_end;
-  const int nkt = (int)((k_end - k_begin + BN - 1) / BN);
+  const int nk = (int)(k_end - k_begin);  // visible keys of the tile (before the per-row causal cut)
+  const int nkt = (nk + BN - 1) / BN;     // key tiles
+  const int nfull = nk / BN;              // of which complete
 
-  const int64_t q_stride = (int64_t)p.Hq * D, kv_stride = (int64_t)p.Hkv * D;
+  const int64_t q_stride = (int64_t)p.Hq * D;
+  const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;  // bytes between consecutive tokens of one kv head
   const __bf16* qbase = p.q + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D;
-  const __bf16* kbase = p.k + ((int64_t)tc.b * p.S * p.Hkv + g) * D;
-  const __bf16* vbase = p.v + ((int64_t)tc.b * p.S * p.Hkv + g) * D;
+  const char* kbase = reinterpret_cast<const char*>(p.k + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D);
+  const char* vbase = reinterpret_cast<const char*>(p.v + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D);
+  const int64_t tile_pitch = BN * kv_pitch;
+
+  const uint32_t lds0 = lds_address(smem);
+  AsyncTile<D> ld;
+  ld.init(tid, kv_pitch);
+  ld.load(lds0, kbase, nk);
+  ld.load(lds0 + TILE_BYTES, vbase, nk);
 
   // This lane's query row (clamped into the tile so that out-of-range lanes repeat the last row).
   int64_t row = q0 + wv * 32 + n;
   const bool row_ok = row < q_end;
   if (!row_ok) row = q_end - 1;
+  const int row_rel = (int)(row - k_begin);  // position of the row among the document's keys
 
   // Q fragments: B operand of S^T = K Q^T, column n = query, k = head-dim index.
   bf16x8 qf[NKS];
@@ -51,32 +65,26 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
   for (int ks = 0; ks < NKS; ++ks)
     qf[ks] = *reinterpret_cast<const bf16x8*>(qbase + row * q_stride + ks * 16 + h * 8);
 
-  // LDS offsets that do not change over the loop.
-  int k_off[2][NKS];  // K tile, A operand: row = key 32j + n, chunk = 2ks + h
+  // Per-lane LDS addresses inside stage 0; stage, tile and row-block offsets are immediates.
+  const char* k_ptr[NKS];  // K tile, A operand: row = key n (+32 for the second block), chunk = 2ks + h
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int ks = 0; ks < NKS; ++ks) k_ptr[ks] = smem + tile_off<D>(n, 2 * ks + h);
+  // V tile, transpose loads: rows 4h..4h+3 (v_ptr0) and 8+4h.. (v_ptr8) of each 16-key group
+  const char* v_ptr0[NDB];
+  const char* v_ptr8[NDB];
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) k_off[j][ks] = tile_off<D>(32 * j + n, 2 * ks + h);
-  // V tile, transpose loads: d block db, key group (j, s, a): rows 32j + 16s + 8a + 4h .. +3
-  const int grp = lane >> 4;  // 16-lane group: grp % 2 picks the 16-column half, grp / 2 == h
-  int v_off[NDB];             // for rows starting at 4h; other row groups add a multiple of 8 rows
-#pragma unroll
-  for (int db = 0; db < NDB; ++db) v_off[db] = tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
-  // Row r0 + 8x keeps the same swizzle when 8x is a multiple of 16 only; so precompute per (x) instead.
-  // swz(r) depends on r & 15, and row groups differ by multiples of 8, so two variants suffice.
-  int v_off8[NDB];
-#pragma unroll
-  for (int db = 0; db < NDB; ++db) v_off8[db] = tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
-
-  TileRegs<BN, D> kr, vr;
-  tile_load<BN, D>(kr, kbase, kv_stride, k_begin, k_end - 1, tid);
-  tile_load<BN, D>(vr, vbase, kv_stride, k_begin, k_end - 1, tid);
-  tile_store<BN, D>(kr, smem, tid);
-  tile_store<BN, D>(vr, smem + TILE_BYTES, tid);
-  __syncthreads();
+  for (int db = 0; db < NDB; ++db) {
+    v_ptr0[db] = smem + TILE_BYTES + tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    v_ptr8[db] = smem + TILE_BYTES + tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+  }
 
   const float c = p.scale_log2;
-  float m = -INFINITY;  // running row maximum of the raw (unscaled) scores
+  // The running reference m only moves when a row maximum exceeds it by more than kSlack (in
+  // log2 units): exponentials then stay below 2^kSlack, the final normalisation by l is exact
+  // either way, and the accumulator is rescaled only a handful of times per row.
+  constexpr float kSlack = 8.0f;
+  const float slack_raw = kSlack / c;
+  float m = -INFINITY;  // reference maximum, raw (unscaled) score units
   float l = 0.f;        // this lane's share of the row sum (its half of the keys)
   f32x16 oacc[NDB];
 #pragma unroll
@@ -84,88 +92,120 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
 
-  const int64_t wave_row_min = q0 + wv * 32;
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int64_t kb = k_begin + (int64_t)kt * BN;
-    const char* ks_lds = smem + (kt & 1) * 2 * TILE_BYTES;
-    const char* vs_lds = ks_lds + TILE_BYTES;
-    const bool more = kt + 1 < nkt;
-    if (more) {
-      tile_load<BN, D>(kr, kbase, kv_stride, kb + BN, k_end - 1, tid);
-      tile_load<BN, D>(vr, vbase, kv_stride, kb + BN, k_end - 1, tid);
-    }
+  const int wave_row_min = (int)(q0 - k_begin) + wv * 32;
 
-    // S^T blocks: rows = keys kb + 32j .. +31, column = this lane's query
-    f32x16 s[2];
+  // One 64-key LDS tile is consumed as two 32-key blocks, each with its own softmax update.
+  // `stage` is the byte offset of the stage holding tile kt; FULL_NEXT says that tile kt+1
+  // exists and is complete (the common case, no per-lane address arithmetic).
+  auto tile_step = [&](const int kt, const int stage, auto full_next) {
+    const int kb = kt * BN;  // first key of the tile, relative to k_begin
+    const uint32_t next_lds = lds0 + (STAGE_BYTES - stage);
+#ifdef IE_EXP_NO_GLOBAL
+    if (false) {
+#else
+    if (full_next) {
+#endif
+      ld.load_full(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch);
+      ld.load_full(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch);
+    } else if (kt + 1 < nkt) {
+      ld.load(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch, nk - kb - BN);
+      ld.load(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch, nk - kb - BN);
+    }
+    // Mask: only tiles that reach past the wave's first row (causal) or past the last key.
+    const bool need_mask = (p.causal && kb + BN - 1 > wave_row_min) || (kb + BN > nk);
+    const int lim = (p.causal ? row_rel : nk - 1) - kb - 4 * h;  // last visible key relative to the lane's first key
+
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
+      // S^T block: rows = keys kb + 32j .. +31, column = this lane's query
+      f32x16 s;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[j][r] = 0.f;
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) s[j] = mfma32(lds_read8(ks_lds, k_off[j][ks]), qf[ks], s[j]);
-    }
-
-    // Mask: only tiles that reach past the wave's first row (causal) or past the last key.
-    const bool need_mask = (p.causal && kb + BN - 1 > wave_row_min) || (kb + BN > k_end);
-    if (need_mask) {
-      const int64_t lim = p.causal ? (row < k_end - 1 ? row : k_end - 1) : k_end - 1;  // last visible key
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int64_t key = kb + 32 * j + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (key > lim) s[j][r] = -INFINITY;
-        }
-    }
-
-    float mx = s[0][0];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[j][r]);
-    mx = halfwave_max(mx);
-    const float m_new = fmaxf(m, mx);
-    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {  // some row's maximum moved: rescale
-      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
-      l *= alpha;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-    }
-    m = m_new;
-    const float mc = m * c;
-    bf16x8 pf[2][2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[j][r], c, -mc));
-        l += e;
-        pf[j][r >> 3][r & 7] = (__bf16)e;
+      for (int ks = 0; ks < NKS; ++ks) {
+#ifdef IE_EXP_NO_LDS
+        s = mfma32(qf[(ks + 1) % NKS], qf[ks], s);
+#else
+        s = mfma32(lds_read8(k_ptr[ks], stage + 32 * j * ROW_BYTES), qf[ks], s);
+#endif
       }
 
-    // O^T += V^T P^T
+      // V^T fragments of this block: requested now, consumed after the exponentials
+      bf16x8 vfrag[2][NDB];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int sblk = 0; sblk < 2; ++sblk) {
-        const int rowbytes = (32 * j + 16 * sblk) * (D * 2);
+      for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
-          bf16x4 lo = lds_read_tr4(vs_lds + rowbytes + v_off[db]);
-          bf16x4 hi = lds_read_tr4(vs_lds + rowbytes + v_off8[db]);
-          oacc[db] = mfma32(cat4(lo, hi), pf[j][sblk], oacc[db]);
+          const int off = stage + (32 * j + 16 * sblk) * ROW_BYTES;
+#ifdef IE_EXP_NO_LDS
+          vfrag[sblk][db] = qf[(db + sblk) % NKS];
+#else
+          vfrag[sblk][db] = cat4(lds_read_tr4(v_ptr0[db] + off), lds_read_tr4(v_ptr8[db] + off));
+#endif
         }
-      }
 
-    if (more) {
-      char* nk = smem + ((kt + 1) & 1) * 2 * TILE_BYTES;
-      tile_store<BN, D>(kr, nk, tid);
-      tile_store<BN, D>(vr, nk + TILE_BYTES, tid);
+      if (need_mask) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (32 * j + 8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
+      }
+#ifdef IE_EXP_NO_SOFTMAX
+      float mx = s[0];
+#else
+      float mx = s[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+      mx = halfwave_max(mx);
+#endif
+      if (__builtin_amdgcn_ballot_w64(mx > m + slack_raw) != 0) {  // some row outgrew its reference
+        const float m_new = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+        m = m_new;
+        l *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+      }
+      const float mc = m * c;
+      bf16x8 pf[2];
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk) {
+        bf16x2 pr[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+#ifdef IE_EXP_NO_SOFTMAX
+          const float e0 = s[8 * sblk + 2 * t], e1 = s[8 * sblk + 2 * t + 1];
+#else
+          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * sblk + 2 * t], c, -mc));
+          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * sblk + 2 * t + 1], c, -mc));
+#endif
+          pr[t] = pack_bf16(e0, e1);
+          l += e0 + e1;  // fp32 sum of the unrounded exponentials: lse needs more than bf16 precision
+        }
+        pf[sblk] = cat_pairs(pr[0], pr[1], pr[2], pr[3]);
+      }
+      // O^T += V^T P^T
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) oacc[db] = mfma32(vfrag[sblk][db], pf[sblk], oacc[db]);
     }
-    __syncthreads();
+    async_wait_all();  // the copies of the next stage have landed ...
+    __syncthreads();   // ... for every wave, and every wave is done reading this stage
+  };
+
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) consume(qf[ks]);
+  async_wait_all();
+  __syncthreads();
+  int kt = 0;
+  // steady state: two tiles per trip so that the stage offsets are compile-time constants
+  for (; kt + 2 < nfull; kt += 2) {
+    tile_step(kt, 0, std::true_type{});
+    tile_step(kt + 1, STAGE_BYTES, std::true_type{});
   }
+  for (; kt < nkt; ++kt) tile_step(kt, (kt & 1) * STAGE_BYTES, std::false_type{});
 
   // Epilogue: normalise, write O (bf16) and LSE (natural log).
   const float l_full = halfwave_sum(l);

@@ -41,6 +41,8 @@ int check_shape(const int32_t* cu, int32_t num_docs, int64_t B, int64_t S, int32
   // element counts must stay far from overflow and the grid below 2^31
   if (B > kMaxElems / S || B * S > kMaxElems / Hq || B * S * Hq > kMaxElems / D) return IE_ERR_SHAPE;
   if (S >= ((int64_t)1 << 31)) return IE_ERR_SHAPE;
+  // the tile loaders address rows with 32-bit byte offsets: one token row of all heads must stay below 16 MiB
+  if ((int64_t)Hq * D * 2 >= ((int64_t)1 << 24)) return IE_ERR_SHAPE;
   return IE_OK;
 }
 
@@ -75,7 +77,7 @@ int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
 size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs) {
   (void)num_docs;
   if (check_shape(nullptr, 0, B, S, Hq, Hkv, D, 1.0f, 1) != IE_OK) return 0;
-  return align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256);  // delta [B,Hq,S]
+  return 2 * align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256);  // delta and lse*log2e, [B,Hq,S] each
 }
 
 int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
@@ -104,6 +106,7 @@ int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* 
   p.dout = static_cast<const __bf16*>(dout);
   p.lse = lse;
   p.delta = static_cast<float*>(workspace);
+  p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 2);
   p.dq = static_cast<__bf16*>(dq);
   p.dk = static_cast<__bf16*>(dk);
   p.dv = static_cast<__bf16*>(dv);
