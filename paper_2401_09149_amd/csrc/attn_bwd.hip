@@ -299,8 +299,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   bf16x8 kf[NKS], vf[NKS];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    kf[ks] = *reinterpret_cast<const bf16x8*>(p.k + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
-    vf[ks] = *reinterpret_cast<const bf16x8*>(p.v + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
+    kf[ks] = global_load_to_agpr(p.k + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
+    vf[ks] = global_load_to_agpr(p.v + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
   }
 
   const char* nat_ptr[NKS];  // row n of a tile, chunk 2ks + h (A operand: Q or dO rows)
@@ -323,32 +323,56 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 
   const float c = p.scale_log2;
 
+  // One step = one 64-row query tile = two 32-row blocks.  With a single wave per SIMD nothing
+  // else hides LDS latency, so each group of operands is requested one phase before the MFMAs
+  // that use it, and in an order that lets a group reuse the registers of the group the
+  // preceding MFMAs have just consumed (at most two groups of 32 registers are live):
+  //   [dO rows] S=QK^T [dO^T] dP=dOV^T [Q^T] P=exp(..) dV+=dO^T P | dS=P(dP-delta) [next Q rows] dK+=Q^T dS
+  // kPin keeps LDS reads from crossing the phase boundaries but lets ALU and MFMA instructions move.
+  constexpr int kPin = 0x1 | 0x2 | 0x4 | 0x8 | 0x400;
   auto step_fn = [&](const int st, const int stage) {
     if (st + 1 < total) issue_step(st + 1, (STAGE_BYTES - stage) / STAGE_BYTES);
     const int i0 = (st % nqt) * BQ;
     // Mask when a key of this wave can exceed a row of the tile (causal) or rows run past the document.
     const bool need_mask = (p.causal && wv * 32 + 31 > i0) || (i0 + BQ > nq);
 
+    bf16x8 qn[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(nat_ptr[ks], stage);
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
       const int blk = stage + 32 * rb * ROW_BYTES;
-      f32x16 s, dp;
+      bf16x8 don[NKS];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+      for (int ks = 0; ks < NKS; ++ks) don[ks] = lds_read8(nat_ptr[ks], blk + TILE_BYTES);
+      __builtin_amdgcn_sched_barrier(kPin);
+      f32x16 s = mfma_chain_b_in_agpr<NKS>(qn, kf);
+      bf16x8 dotf[2][NDB];
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) s = mfma32(lds_read8(nat_ptr[ks], blk), kf[ks], s);
+      for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) dp = mfma32(lds_read8(nat_ptr[ks], blk + TILE_BYTES), vf[ks], dp);
-      // transposed operands of the two accumulating products, requested before the elementwise work
-      bf16x8 dotf[2][NDB], qtf[2][NDB];
+        for (int db = 0; db < NDB; ++db) {
+          const int off = blk + 16 * sblk * ROW_BYTES + TILE_BYTES;
+          dotf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off), lds_read_tr4(tr_ptr8[db] + off));
+        }
+      __builtin_amdgcn_sched_barrier(kPin);
+      f32x16 dp = mfma_chain_b_in_agpr<NKS>(don, vf);
+      bf16x8 qtf[2][NDB];
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const int off = blk + 16 * sblk * ROW_BYTES;
-          dotf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off + TILE_BYTES), lds_read_tr4(tr_ptr8[db] + off + TILE_BYTES));
           qtf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off), lds_read_tr4(tr_ptr8[db] + off));
         }
+      // row statistics of the block's 16 rows held by this lane
+      f32x4 l4[4], d4[4];
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        l4[q4] = *reinterpret_cast<const f32x4*>(stat_ptr + stage + (32 * rb + 8 * q4) * 4);
+        d4[q4] = *reinterpret_cast<const f32x4*>(stat_ptr + stage + (BQ + 32 * rb + 8 * q4) * 4);
+      }
+      __builtin_amdgcn_sched_barrier(kPin);
       if (need_mask) {
         const int lim_c = p.causal ? key_rel - i0 - 32 * rb - 4 * h : -(1 << 30);  // rows below this see no key of the lane
         const int lim_e = nq - i0 - 32 * rb - 4 * h;                                // rows from here on do not exist
@@ -358,41 +382,51 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
           if (ri < lim_c || ri >= lim_e) s[r] = -INFINITY;
         }
       }
-      bf16x8 pf[2], dsf[2];
+      float pr[16];
+      bf16x8 pf[2];
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk) {
-        bf16x2 pp[4], dd[4];
+        bf16x2 pp[4];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const int q4 = 2 * sblk + half;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat_ptr + stage + (32 * rb + 8 * q4) * 4);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat_ptr + stage + (BQ + 32 * rb + 8 * q4) * 4);
-#pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2) {
-            const int r = 4 * q4 + 2 * t2;
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[2 * t2]));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], c, -l4[2 * t2 + 1]));
-            pp[2 * half + t2] = pack_bf16(p0, p1);
-            dd[2 * half + t2] = pack_bf16(p0 * (dp[r] - d4[2 * t2]), p1 * (dp[r + 1] - d4[2 * t2 + 1]));
-          }
+        for (int t = 0; t < 4; ++t) {
+          const int r = 8 * sblk + 2 * t;
+          pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[r >> 2][r & 3]));
+          pr[r + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], c, -l4[r >> 2][(r & 3) + 1]));
+          pp[t] = pack_bf16(pr[r], pr[r + 1]);
         }
         pf[sblk] = cat_pairs(pp[0], pp[1], pp[2], pp[3]);
-        dsf[sblk] = cat_pairs(dd[0], dd[1], dd[2], dd[3]);
       }
 #pragma unroll
-      for (int sblk = 0; sblk < 2; ++sblk) {
+      for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) dvacc[db] = mfma32(dotf[sblk][db], pf[sblk], dvacc[db]);
+      bf16x8 dsf[2];
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk) {
+        bf16x2 dd[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int r = 8 * sblk + 2 * t;
+          dd[t] = pack_bf16(pr[r] * (dp[r] - d4[r >> 2][r & 3]), pr[r + 1] * (dp[r + 1] - d4[r >> 2][(r & 3) + 1]));
+        }
+        dsf[sblk] = cat_pairs(dd[0], dd[1], dd[2], dd[3]);
+      }
+      // row-major Q fragments of the next block ride along with this block's last product
+      if (rb == 0) {
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(nat_ptr[ks], stage + 32 * ROW_BYTES);
+      }
+      __builtin_amdgcn_sched_barrier(kPin);
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) dkacc[db] = mfma32(qtf[sblk][db], dsf[sblk], dkacc[db]);
-      }
     }
     async_wait_all();
     __syncthreads();
   };
 
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) { consume(kf[ks]); consume(vf[ks]); }
+  agpr_loads_wait();  // K/V fragments (and the first stage's copies) have arrived
   async_wait_all();
   __syncthreads();
   int st = 0;

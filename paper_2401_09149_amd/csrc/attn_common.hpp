@@ -52,6 +52,55 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// acc = sum_ks A[ks] * B[ks] with the B fragments held in accumulation registers (AGPRs).
+// Kernels that run one wave per SIMD keep their stationary operands there: the register
+// file has 256 architectural + 256 accumulation registers per lane, but left to itself the
+// compiler parks such operands in AGPRs and copies them back (v_accvgpr_read) in front of
+// every MFMA, which costs four VALU slots per MFMA.  Written as one assembly block the MFMAs
+// read the AGPRs directly.  The block ends with the wait states an 8-pass MFMA needs before
+// a VALU instruction may read its result (the compiler's hazard recogniser does not look
+// inside inline assembly).
+template <int NKS>
+__device__ __forceinline__ f32x16 mfma_chain_b_in_agpr(const bf16x8 (&a)[NKS], const bf16x8 (&b)[NKS]) {
+  f32x16 acc;
+  static_assert(NKS == 8 || NKS == 4, "head dimension 128 or 64");
+  if constexpr (NKS == 8) {
+    asm volatile(
+        "v_mfma_f32_32x32x16_bf16 %0, %1, %9, 0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %2, %10, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %3, %11, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %4, %12, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %5, %13, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %6, %14, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %7, %15, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %8, %16, %0\n\t"
+        "s_nop 15"
+        : "=&v"(acc)
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]),
+          "a"(b[0]), "a"(b[1]), "a"(b[2]), "a"(b[3]), "a"(b[4]), "a"(b[5]), "a"(b[6]), "a"(b[7]));
+  } else {
+    asm volatile(
+        "v_mfma_f32_32x32x16_bf16 %0, %1, %5, 0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %2, %6, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %3, %7, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %4, %8, %0\n\t"
+        "s_nop 15"
+        : "=&v"(acc)
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "a"(b[0]), "a"(b[1]), "a"(b[2]), "a"(b[3]));
+  }
+  return acc;
+}
+
+// 16-byte global load straight into accumulation registers (for operands that stay there
+// for the whole kernel).  The compiler does not know this is a load: call agpr_loads_wait()
+// before the first use.
+__device__ __forceinline__ bf16x8 global_load_to_agpr(const void* ptr) {
+  bf16x8 r;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(r) : "v"(ptr) : "memory");
+  return r;
+}
+__device__ __forceinline__ void agpr_loads_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Exchange between the two half-waves with v_permlane32_swap: given (a, b) it returns
 // r0 = {a[0..31], b[0..31]} and r1 = {a[32..63], b[32..63]}.  With a == b == x, lane l
 // sees x[l] and x[l ^ 32] in (r0, r1) (in some order).  The vector elements are copied to
