@@ -35,6 +35,17 @@ def event_ms(fn, iters):
     return sum(ts) / len(ts), min(ts)
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` (fetch + write), from the committed rocprofv3 counter summary
+    of this workload, or None when no summary has been recorded."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.json")
+    try:
+        with open(path) as f:
+            return json.load(f)["bytes_per_launch"].get(kernel)
+    except (OSError, ValueError, KeyError):
+        return None
+
+
 def cpu_baseline(cfg, q, k, v, dout, prefix, heads):
     """fp64 oracle, all three passes, on the causal prefix [0, prefix) of the first `heads` heads."""
     import numpy as np
@@ -69,6 +80,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-prefix", type=int, default=32768)
     ap.add_argument("--cpu-heads", type=int, default=2)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -101,6 +114,14 @@ def main():
     def step():
         fwd()
         bwd()
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)     # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -139,7 +160,7 @@ def main():
     dom_ms, dom_flop = kernels[dom]
     achieved = dom_flop / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "ms": dom_ms}
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg.name, dom), "ms": dom_ms}
 
     out = {
         "metric": "causal attention fwd+bwd TFLOPS and % of bf16 MFMA peak, 1 MI355X, S=32K D=128",

@@ -1,0 +1,94 @@
+// Measures what the bf16 matrix cores of this GPU sustain, as the denominator's reality check:
+// a register-only loop of v_mfma_f32_32x32x16_bf16 (no memory, no LDS, no VALU work), four
+// independent accumulators per wave, one wave per SIMD on every CU, run for a few seconds so
+// that power management has settled.  Two operand regimes: small integers that never change
+// (little switching activity), and N(0,1)-like values cycling through 8 register sets so that
+// consecutive MFMAs see different inputs, as in a real contraction.
+//
+// Prints TFLOP/s and the clock that figure implies at 1024 FLOP/clk/SIMD x 4 SIMD x 256 CU.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
+
+#define CK(x)                                                                          \
+  do {                                                                                 \
+    hipError_t e = (x);                                                                \
+    if (e != hipSuccess) {                                                             \
+      std::printf("HIP error %s at line %d\n", hipGetErrorString(e), __LINE__);        \
+      std::exit(1);                                                                    \
+    }                                                                                  \
+  } while (0)
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ float pseudo_normal(unsigned& h) {  // sum of three uniforms, unit-ish variance
+  float s = 0.f;
+  for (int i = 0; i < 3; ++i) {
+    h = h * 1664525u + 1013904223u;
+    s += (h >> 8) * (1.0f / 16777216.0f);
+  }
+  return (s - 1.5f) * 2.0f;
+}
+
+template <int NSET, bool RANDOM>
+__global__ __launch_bounds__(256) void mfma_loop(float* out, int iters) {
+  const int tid = threadIdx.x;
+  unsigned h = tid * 2654435761u + blockIdx.x * 40503u + 12345u;
+  bf16x8 a[NSET], b[NSET];
+  for (int i = 0; i < NSET; ++i)
+    for (int t = 0; t < 8; ++t) {
+      a[i][t] = RANDOM ? (__bf16)pseudo_normal(h) : (__bf16)(float)((tid * 7 + t) % 5 - 2);
+      b[i][t] = RANDOM ? (__bf16)pseudo_normal(h) : (__bf16)(float)((tid + t) % 3 - 1);
+    }
+  f32x16 c[4];
+  for (int i = 0; i < 4; ++i)
+    for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      c[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u % NSET], b[(u / 4 + u) % NSET], c[u & 3], 0, 0, 0);
+  }
+  float s = 0.f;
+  for (int i = 0; i < 4; ++i)
+    for (int r = 0; r < 16; ++r) s += c[i][r];
+  out[blockIdx.x * 256 + tid] = s;
+}
+
+template <int NSET, bool RANDOM>
+void run(float* out, int cus, const char* name, double seconds) {
+  const int iters = 20000;  // 16 MFMAs of 32768 FLOP per trip and wave
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  float ms = 0.f;
+  const auto t0 = std::chrono::steady_clock::now();
+  double elapsed = 0.0;
+  while (elapsed < seconds) {
+    CK(hipEventRecord(e0));
+    mfma_loop<NSET, RANDOM><<<cus, 256>>>(out, iters);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    elapsed = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  }
+  const double flop = (double)cus * 4 * iters * 16 * 32768.0;
+  const double tflops = flop / (ms * 1e-3) / 1e12;
+  const double ghz = tflops * 1e12 / ((double)cus * 4 * 1024.0) / 1e9;
+  std::printf("%-52s %8.1f TFLOP/s after %.1f s  (= %.2f GHz at 1024 FLOP/clk/SIMD)\n", name, tflops, elapsed, ghz);
+}
+
+int main(int argc, char** argv) {
+  const double seconds = argc > 1 ? std::atof(argv[1]) : 3.0;
+  hipDeviceProp_t prop;
+  CK(hipGetDeviceProperties(&prop, 0));
+  std::printf("device: %s, %d CUs, clock rate %.2f GHz\n", prop.gcnArchName, prop.multiProcessorCount, prop.clockRate / 1e6);
+  float* out;
+  CK(hipMalloc(&out, (size_t)prop.multiProcessorCount * 256 * sizeof(float)));
+  run<1, false>(out, prop.multiProcessorCount, "32x32x16 bf16, constant small-integer operands", seconds);
+  run<8, true>(out, prop.multiProcessorCount, "32x32x16 bf16, N(0,1) operands, 8 sets cycled", seconds);
+  CK(hipFree(out));
+  return 0;
+}
