@@ -16,6 +16,7 @@
 
 #include "attn_common.hpp"
 #include "launch.hpp"
+#include "mfma_asm.hpp"
 
 namespace ie {
 
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
 
   const int wave_row_min = (int)(q0 - k_begin) + wv * 32;
 
-  auto tile_step = [&](const int kt, const int stage, auto full_next) {
+  auto tile_step = [&](const int kt, const int stage, auto full_next) __attribute__((always_inline)) {
     const int kb = kt * BN;
     const uint32_t next_lds = lds0 + (STAGE_BYTES - stage);
     if (full_next) {
@@ -227,9 +228,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
 // same accumulators, which is the GQA reduction.
 template <int D>
 struct DkdvCfg {
-  static constexpr int BK = 128, BQ = 64;
+  static constexpr int BK = 128;                                  // keys per workgroup
+  static constexpr int BQ = 128;                                  // query rows per loop step
+  static constexpr int NB = BQ / 32;                              // 32-row blocks per step
   static constexpr int TILE_BYTES = BQ * D * 2;
-  static constexpr int STAT_BYTES = 2 * BQ * 4;                   // lse*log2e [64], delta [64]
+  static constexpr int STAT_BYTES = 2 * BQ * 4;                   // lse*log2e [BQ], delta [BQ]
   static constexpr int STAGE_BYTES = 2 * TILE_BYTES + STAT_BYTES; // Q, dO, stats
   static constexpr int STAGES = 2;
   static constexpr int SMEM_BYTES = STAGES * STAGE_BYTES;
@@ -238,7 +241,7 @@ struct DkdvCfg {
 template <int D>
 __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p) {
   using C = DkdvCfg<D>;
-  constexpr int BK = C::BK, BQ = C::BQ;
+  constexpr int BK = C::BK, BQ = C::BQ, NB = C::NB;
   constexpr int NKS = D / 16, NDB = D / 32;
   constexpr int TILE_BYTES = C::TILE_BYTES, STAGE_BYTES = C::STAGE_BYTES;
   constexpr int ROW_BYTES = D * 2;
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   const int wave_u = ld.wave;
 
   // Asynchronous copy of step `st` (query head, query tile) into stage `slot`.
-  auto issue_step = [&](const int st, const int slot) {
+  auto issue_step = [&](const int st, const int slot) __attribute__((always_inline)) {
     const int hq = g * group + st / nqt;
     const int i0 = (st % nqt) * BQ;  // first row of the tile, relative to q_begin
     const int rows = nq - i0;        // valid rows (>= 1)
@@ -276,16 +279,27 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     const char* qg = reinterpret_cast<const char*>(p.q + (tok * p.Hq + hq) * D);
     const char* dog = reinterpret_cast<const char*>(p.dout + (tok * p.Hq + hq) * D);
     const uint32_t base = lds0 + slot * STAGE_BYTES;
-    ld.load(base, qg, rows);
-    ld.load(base + TILE_BYTES, dog, rows);
-    // statistics: wave 0 copies lse*log2e, wave 1 copies delta (one dword per lane = one row)
-    if (wave_u < 2) {
-      int r = lane < rows ? lane : rows - 1;
+#pragma unroll
+    for (int part = 0; part < BQ / 64; ++part) {
+      // rows past the end repeat the last valid row (masked later); a part that lies entirely
+      // past the end repeats it 64 times
+      const int first = rows > 64 * part ? 64 * part : rows - 1;
+      const int valid = rows > 64 * part ? rows - 64 * part : 1;
+      ld.load(base + part * 64 * ROW_BYTES, qg + (int64_t)first * q_pitch, valid);
+      ld.load(base + TILE_BYTES + part * 64 * ROW_BYTES, dog + (int64_t)first * q_pitch, valid);
+    }
+    // statistics, one dword per lane = one row: waves 0,1 copy lse*log2e of rows 0-63, 64-127;
+    // waves 2,3 copy delta
+    {
+      const int half = wave_u & 1;
+      int r = 64 * half + lane;
+      r = r < rows ? r : rows - 1;
       const int64_t idx = ((int64_t)tc.b * p.Hq + hq) * p.S + q_begin + i0;
-      const float* src = (wave_u == 0 ? p.lse2 : p.delta) + idx;
+      const char* src = uniform(reinterpret_cast<const char*>((wave_u < 2 ? p.lse2 : p.delta) + idx));
+      const uint32_t dst = uniform(base + 2 * TILE_BYTES + (wave_u < 2 ? 0 : BQ * 4) + half * 256);
       asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                    :
-                   : "v"((uint32_t)r * 4u), "s"(src), "s"(base + 2 * TILE_BYTES + wave_u * BQ * 4)
+                   : "v"((uint32_t)r * 4u), "s"(src), "s"(dst)
                    : "memory");
     }
   };
@@ -296,26 +310,34 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   const bool key_ok = key < tc.doc_end;
   const int64_t key_ld = key_ok ? key : tc.doc_end - 1;
   const int key_rel = (int)(key - q_begin);  // position of the key among the rows that see the tile
-  bf16x8 kf[NKS], vf[NKS];
+  bf16x8 kf[NKS], vf[NKS];                   // live in AGPRs
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     kf[ks] = global_load_to_agpr(p.k + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
     vf[ks] = global_load_to_agpr(p.v + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
   }
 
-  const char* nat_ptr[NKS];  // row n of a tile, chunk 2ks + h (A operand: Q or dO rows)
+  // Per-lane LDS addresses for each stage; block, tile and k-step offsets are immediates.
+  struct StagePtrs {
+    const char* nat[NKS];   // row n of a tile, chunk 2ks + h (A operand: Q or dO rows)
+    const char* tr0[NDB];   // transpose loads, rows 4h.. of a 16-row group
+    const char* tr8[NDB];   // rows 8 + 4h..
+    const char* stat;       // this half-wave's 4-row groups of the statistics
+  } sp[2];
 #pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) nat_ptr[ks] = smem + tile_off<D>(n, 2 * ks + h);
-  const char* tr_ptr0[NDB];
-  const char* tr_ptr8[NDB];
+  for (int stg = 0; stg < 2; ++stg) {
+    const char* b = smem + stg * STAGE_BYTES;
 #pragma unroll
-  for (int db = 0; db < NDB; ++db) {
-    tr_ptr0[db] = smem + tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
-    tr_ptr8[db] = smem + tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    for (int ks = 0; ks < NKS; ++ks) sp[stg].nat[ks] = b + tile_off<D>(n, 2 * ks + h);
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      sp[stg].tr0[db] = b + tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+      sp[stg].tr8[db] = b + tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    }
+    sp[stg].stat = b + 2 * TILE_BYTES + 16 * h;
   }
-  const char* stat_ptr = smem + 2 * TILE_BYTES + 16 * h;  // this half-wave's 4-row groups of the statistics
 
-  f32x16 dkacc[NDB], dvacc[NDB];
+  f32x16 dkacc[NDB], dvacc[NDB];  // live in AGPRs
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -323,28 +345,120 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 
   const float c = p.scale_log2;
 
-  // One step = one 64-row query tile = two 32-row blocks.  With a single wave per SIMD nothing
-  // else hides LDS latency, so each group of operands is requested one phase before the MFMAs
-  // that use it, and in an order that lets a group reuse the registers of the group the
-  // preceding MFMAs have just consumed (at most two groups of 32 registers are live):
-  //   [dO rows] S=QK^T [dO^T] dP=dOV^T [Q^T] P=exp(..) dV+=dO^T P | dS=P(dP-delta) [next Q rows] dK+=Q^T dS
-  // kPin keeps LDS reads from crossing the phase boundaries but lets ALU and MFMA instructions move.
-  constexpr int kPin = 0x1 | 0x2 | 0x4 | 0x8 | 0x400;
-  auto step_fn = [&](const int st, const int stage) {
-    if (st + 1 < total) issue_step(st + 1, (STAGE_BYTES - stage) / STAGE_BYTES);
-    const int i0 = (st % nqt) * BQ;
-    // Mask when a key of this wave can exceed a row of the tile (causal) or rows run past the document.
-    const bool need_mask = (p.causal && wv * 32 + 31 > i0) || (i0 + BQ > nq);
-
+  // Unmasked tile, hand-sequenced (see mfma_asm.hpp).  Per 32-row block the 32 MFMAs run back
+  // to back and the elementwise work rides in their shadow, at least two MFMAs behind the
+  // chain whose result it needs:
+  //   M0-7   S  = Q K^T                      (bare)          LDS: dO rows, lse -> needed from M8
+  //   M8-15  dP = dO V^T      + P pairs 0..5 from M10 on     LDS: dO^T, delta  -> needed from M16
+  //   M16-23 dV += dO^T P     + P pairs 6,7; dS pairs 0..5 from M18 on     LDS: Q^T -> M24
+  //   M24-31 dK += Q^T dS     + dS pairs 6,7                 LDS: Q rows of the next block
+  auto fast_tile = [&](const StagePtrs& sp_) __attribute__((always_inline)) {
+    static_assert(NDB == 4 || NDB == 2, "pair schedule below is written for D = 128 (used) and compiles for 64");
     bf16x8 qn[NKS];
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(nat_ptr[ks], stage);
+    for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], 0);
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      const int blk = stage + 32 * rb * ROW_BYTES;
+    for (int rb = 0; rb < NB; ++rb) {
+      const int blk = 32 * rb * ROW_BYTES;
       bf16x8 don[NKS];
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) don[ks] = lds_read8(nat_ptr[ks], blk + TILE_BYTES);
+      for (int ks = 0; ks < NKS; ++ks) don[ks] = lds_read8(sp_.nat[ks], blk + TILE_BYTES);
+      f32x4 l4[4];
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) l4[q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (32 * rb + 8 * q4) * 4);
+      asm_fence();
+      f32x16 s, dp;
+      mfma_first_b_agpr(s, qn[0], kf[0]);
+#pragma unroll
+      for (int ks = 1; ks < NKS; ++ks) mfma_next_b_agpr(s, qn[ks], kf[ks]);
+      asm_fence();
+      bf16x8 dotf[2][NDB];
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const int off = blk + 16 * sblk * ROW_BYTES + TILE_BYTES;
+          dotf[sblk][db] = cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
+        }
+      f32x4 d4[4];
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) d4[q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (BQ + 32 * rb + 8 * q4) * 4);
+      asm_fence();
+      float pr[16];
+      uint32_t pw[8], dw[8];
+      auto p_pair = [&](int g2, auto lead) __attribute__((always_inline)) {
+        const int r = 2 * g2;
+        softmax_pair<decltype(lead)::value>(pr[r], pr[r + 1], pw[g2], s[r], s[r + 1], c, l4[r >> 2][r & 3], l4[r >> 2][(r & 3) + 1]);
+      };
+      auto ds_pair = [&](int g2, auto lead) __attribute__((always_inline)) {
+        const int r = 2 * g2;
+        dscore_pair<decltype(lead)::value>(dw[g2], pr[r], pr[r + 1], dp[r], dp[r + 1], d4[r >> 2][r & 3], d4[r >> 2][(r & 3) + 1]);
+      };
+      // dP chain with the probabilities of pairs 0..5 behind MFMAs 2..7
+      mfma_first_b_agpr(dp, don[0], vf[0]);
+#pragma unroll
+      for (int ks = 1; ks < NKS; ++ks) {
+        mfma_next_b_agpr(dp, don[ks], vf[ks]);
+        if (ks == 2) p_pair(0, std::true_type{});
+        if (ks > 2) p_pair(ks - 2, std::false_type{});
+      }
+      asm_fence();
+      bf16x8 qtf[2][NDB];
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const int off = blk + 16 * sblk * ROW_BYTES;
+          qtf[sblk][db] = cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
+        }
+      asm_fence();
+      // dV chain: P of rows 0-15 is ready; pairs 6,7 follow MFMAs 0,1; dS pairs 0..5 follow MFMAs 2..7
+      const bf16x8 pf0 = frag_from_words(pw[0], pw[1], pw[2], pw[3]);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        mfma_acc_agpr(dvacc[db], dotf[0][db], pf0);
+        if (db < 2) p_pair(6 + db, std::false_type{});
+        if (db == 2) ds_pair(0, std::true_type{});
+        if (db == 3) ds_pair(1, std::false_type{});
+      }
+      const bf16x8 pf1 = frag_from_words(pw[4], pw[5], pw[6], pw[7]);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        mfma_acc_agpr(dvacc[db], dotf[1][db], pf1);
+        ds_pair(2 + db, std::false_type{});
+      }
+      asm_fence();
+      // Q rows of the next block ride along with the dK chain
+      if (rb + 1 < NB) {
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], blk + 32 * ROW_BYTES);
+      }
+      asm_fence();
+      const bf16x8 dsf0 = frag_from_words(dw[0], dw[1], dw[2], dw[3]);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        mfma_acc_agpr(dkacc[db], qtf[0][db], dsf0);
+        if (db < 2) ds_pair(6 + db, std::false_type{});
+      }
+      const bf16x8 dsf1 = frag_from_words(dw[4], dw[5], dw[6], dw[7]);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) mfma_acc_agpr(dkacc[db], qtf[1][db], dsf1);
+    }
+  };
+
+  // Generic tile (diagonal, document end, D = 64): compiler-scheduled, with masks.
+  // kPin keeps LDS reads from crossing the phase boundaries but lets ALU and MFMA instructions move.
+  constexpr int kPin = 0x1 | 0x2 | 0x4 | 0x8 | 0x400;
+  auto generic_tile = [&](const StagePtrs& sp_, const int i0) __attribute__((always_inline)) {
+    bf16x8 qn[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], 0);
+#pragma unroll
+    for (int rb = 0; rb < NB; ++rb) {
+      const int blk = 32 * rb * ROW_BYTES;
+      bf16x8 don[NKS];
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) don[ks] = lds_read8(sp_.nat[ks], blk + TILE_BYTES);
       __builtin_amdgcn_sched_barrier(kPin);
       f32x16 s = mfma_chain_b_in_agpr<NKS>(qn, kf);
       bf16x8 dotf[2][NDB];
@@ -353,7 +467,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const int off = blk + 16 * sblk * ROW_BYTES + TILE_BYTES;
-          dotf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off), lds_read_tr4(tr_ptr8[db] + off));
+          dotf[sblk][db] = cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
         }
       __builtin_amdgcn_sched_barrier(kPin);
       f32x16 dp = mfma_chain_b_in_agpr<NKS>(don, vf);
@@ -363,17 +477,17 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const int off = blk + 16 * sblk * ROW_BYTES;
-          qtf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off), lds_read_tr4(tr_ptr8[db] + off));
+          qtf[sblk][db] = cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
         }
       // row statistics of the block's 16 rows held by this lane
       f32x4 l4[4], d4[4];
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        l4[q4] = *reinterpret_cast<const f32x4*>(stat_ptr + stage + (32 * rb + 8 * q4) * 4);
-        d4[q4] = *reinterpret_cast<const f32x4*>(stat_ptr + stage + (BQ + 32 * rb + 8 * q4) * 4);
+        l4[q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (32 * rb + 8 * q4) * 4);
+        d4[q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (BQ + 32 * rb + 8 * q4) * 4);
       }
       __builtin_amdgcn_sched_barrier(kPin);
-      if (need_mask) {
+      {
         const int lim_c = p.causal ? key_rel - i0 - 32 * rb - 4 * h : -(1 << 30);  // rows below this see no key of the lane
         const int lim_e = nq - i0 - 32 * rb - 4 * h;                                // rows from here on do not exist
 #pragma unroll
@@ -411,10 +525,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
         }
         dsf[sblk] = cat_pairs(dd[0], dd[1], dd[2], dd[3]);
       }
-      // row-major Q fragments of the next block ride along with this block's last product
-      if (rb == 0) {
+      if (rb + 1 < NB) {
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(nat_ptr[ks], stage + 32 * ROW_BYTES);
+        for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], blk + 32 * ROW_BYTES);
       }
       __builtin_amdgcn_sched_barrier(kPin);
 #pragma unroll
@@ -422,6 +535,17 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
         for (int db = 0; db < NDB; ++db) dkacc[db] = mfma32(qtf[sblk][db], dsf[sblk], dkacc[db]);
     }
+  };
+
+  // One step = one query tile of one query head.  `slot` (compile-time) is the stage that holds it.
+  auto step_fn = [&](const int st, auto slot_c) __attribute__((always_inline)) {
+    constexpr int slot = decltype(slot_c)::value;
+    if (st + 1 < total) issue_step(st + 1, 1 - slot);
+    const int i0 = (st % nqt) * BQ;
+    // Mask when a key of this wave can exceed a row of the tile (causal) or rows run past the document.
+    const bool need_mask = (p.causal && wv * 32 + 31 > i0) || (i0 + BQ > nq);
+    if (D == 128 && !need_mask) fast_tile(sp[slot]);
+    else generic_tile(sp[slot], i0);
     async_wait_all();
     __syncthreads();
   };
@@ -431,10 +555,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   __syncthreads();
   int st = 0;
   for (; st + 1 < total; st += 2) {
-    step_fn(st, 0);
-    step_fn(st + 1, STAGE_BYTES);
+    step_fn(st, std::integral_constant<int, 0>{});
+    step_fn(st + 1, std::integral_constant<int, 1>{});
   }
-  if (st < total) step_fn(st, 0);
+  if (st < total) step_fn(st, std::integral_constant<int, 0>{});
+  mfma_result_fence();  // the last assembly MFMAs have retired before the accumulators are read
 
   if (key_ok) {
     __bf16* dkrow = p.dk + kvhead + key * kv_stride;

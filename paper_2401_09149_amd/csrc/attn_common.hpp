@@ -210,7 +210,22 @@ __device__ __forceinline__ void tile_store(const TileRegs<ROWS, D>& t, char* lds
 // must call async_wait_all() before the barrier that publishes a filled stage.  M0 is written
 // without telling the compiler (it is a reserved register that cannot be listed as a clobber);
 // nothing else in these kernels uses M0.
+// Values that are the same in every lane but that the compiler cannot prove uniform (they
+// came through LDS or a per-lane load) are moved to scalar registers explicitly; for values it
+// already keeps in scalar registers this folds away.
+__device__ __forceinline__ uint32_t uniform(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ const char* uniform(const char* p) {
+  const uint64_t x = (uint64_t)p;
+  // the builtin returns a signed int: narrow to 32 unsigned bits before widening, or the low
+  // word's sign bit smears over the high word
+  const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)x);
+  const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+  return (const char*)(lo | (hi << 32));
+}
+
 __device__ __forceinline__ void async_copy16(uint32_t voffset, const char* sbase, uint32_t lds_addr) {
+  sbase = uniform(sbase);
+  lds_addr = uniform(lds_addr);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(voffset), "s"(sbase), "s"(lds_addr)

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
   // One 64-key LDS tile is consumed as two 32-key blocks, each with its own softmax update.
   // `stage` is the byte offset of the stage holding tile kt; FULL_NEXT says that tile kt+1
   // exists and is complete (the common case, no per-lane address arithmetic).
-  auto tile_step = [&](const int kt, const int stage, auto full_next) {
+  auto tile_step = [&](const int kt, const int stage, auto full_next) __attribute__((always_inline)) {
     const int kb = kt * BN;  // first key of the tile, relative to k_begin
     const uint32_t next_lds = lds0 + (STAGE_BYTES - stage);
 #ifdef IE_EXP_NO_GLOBAL

@@ -1,0 +1,72 @@
+// Single-instruction assembly wrappers used where the instruction ORDER is part of the design:
+// a kernel that runs one wave per SIMD can only overlap its elementwise arithmetic with its
+// matrix products if the two are interleaved in program order (one MFMA, then the handful of
+// VALU instructions its 32-cycle shadow can hide), and its stationary operands and
+// accumulators have to stay in AGPRs without being copied back and forth.  Every statement
+// is `asm volatile`, so the compiler keeps them in source order; it still allocates the
+// registers and places the LDS waits for their inputs.
+//
+// Hazards the compiler cannot see inside assembly are handled here by construction:
+//  - a VALU instruction may read an MFMA result only 11 wait states after an 8-pass MFMA was
+//    issued; the groups that consume a chain's result take a `lead` argument that prepends
+//    an s_nop covering that distance, and the kernels place them at least two MFMAs behind
+//    the chain's last MFMA anyway;
+//  - a non-transcendental VALU instruction needs one wait state after the v_exp_f32 whose
+//    result it reads (s_nop 0 in softmax_pair).
+#pragma once
+#include "attn_common.hpp"
+
+namespace ie {
+
+// acc(VGPR) = A(VGPR) * B(AGPR)
+__device__ __forceinline__ void mfma_first_b_agpr(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
+}
+// acc(VGPR) += A(VGPR) * B(AGPR)
+__device__ __forceinline__ void mfma_next_b_agpr(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+}
+// acc(AGPR) += A(VGPR) * B(VGPR)
+__device__ __forceinline__ void mfma_acc_agpr(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// Pins the compiler's own memory instructions (LDS reads) to this point of the sequence.
+__device__ __forceinline__ void asm_fence() { asm volatile("" ::: "memory"); }
+__device__ __forceinline__ void mfma_result_fence() { asm volatile("s_nop 15\n\ts_nop 3" ::: "memory"); }
+
+// p0 = exp2(s0*c - l0), p1 = exp2(s1*c - l1), packed = {bf16(p0), bf16(p1)}
+template <bool LEAD>
+__device__ __forceinline__ void softmax_pair(float& p0, float& p1, uint32_t& packed, float s0, float s1, float c,
+                                             float l0, float l1) {
+  if (LEAD) asm volatile("s_nop 9");
+  asm volatile(
+      "v_fma_f32 %0, %3, %5, -%6\n\t"
+      "v_fma_f32 %1, %4, %5, -%7\n\t"
+      "v_exp_f32 %0, %0\n\t"
+      "v_exp_f32 %1, %1\n\t"
+      "s_nop 0\n\t"
+      "v_cvt_pk_bf16_f32 %2, %0, %1"
+      : "=&v"(p0), "=&v"(p1), "=&v"(packed)
+      : "v"(s0), "v"(s1), "s"(c), "v"(l0), "v"(l1));
+}
+// packed = {bf16(p0 * (dp0 - d0)), bf16(p1 * (dp1 - d1))}
+template <bool LEAD>
+__device__ __forceinline__ void dscore_pair(uint32_t& packed, float p0, float p1, float dp0, float dp1, float d0, float d1) {
+  if (LEAD) asm volatile("s_nop 9");
+  float t0, t1;
+  asm volatile(
+      "v_sub_f32 %0, %5, %7\n\t"
+      "v_sub_f32 %1, %6, %8\n\t"
+      "v_mul_f32 %0, %0, %3\n\t"
+      "v_mul_f32 %1, %1, %4\n\t"
+      "v_cvt_pk_bf16_f32 %2, %0, %1"
+      : "=&v"(t0), "=&v"(t1), "=&v"(packed)
+      : "v"(p0), "v"(p1), "v"(dp0), "v"(dp1), "v"(d0), "v"(d1));
+}
+
+__device__ __forceinline__ bf16x8 frag_from_words(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  u32x4 w = {a, b, c, d};
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+}  // namespace ie
