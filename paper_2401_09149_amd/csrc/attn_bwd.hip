@@ -346,103 +346,107 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   const float c = p.scale_log2;
 
   // Unmasked tile, hand-sequenced (see mfma_asm.hpp).  Per 32-row block the 32 MFMAs run back
-  // to back and the elementwise work rides in their shadow, at least two MFMAs behind the
-  // chain whose result it needs:
-  //   M0-7   S  = Q K^T                      (bare)          LDS: dO rows, lse -> needed from M8
-  //   M8-15  dP = dO V^T      + P pairs 0..5 from M10 on     LDS: dO^T, delta  -> needed from M16
-  //   M16-23 dV += dO^T P     + P pairs 6,7; dS pairs 0..5 from M18 on     LDS: Q^T -> M24
-  //   M24-31 dK += Q^T dS     + dS pairs 6,7                 LDS: Q rows of the next block
+  // to back; the elementwise work rides in their shadow at least two MFMAs behind the chain
+  // whose result it needs, and the LDS reads are spread one or two per MFMA instead of being
+  // issued in bursts (a wave issues in order: a burst of 32 reads holds back the MFMAs behind
+  // it for as long as the LDS pipe needs to drain them).  Every operand group is requested two
+  // chains before the chain that consumes it:
+  //   chain   MFMAs                 VALU in the shadow              LDS reads issued
+  //   S       M0-7   S  = Q K^T                                     dO^T (block b), delta (b)
+  //   dP      M8-15  dP = dO V^T    P pairs 0..5 from M10           Q^T (b)
+  //   dV      M16-23 dV += dO^T P   P pairs 6,7; dS pairs 0..5      Q rows (b+1)
+  //   dK      M24-31 dK += Q^T dS   dS pairs 6,7                    dO rows (b+1), lse (b+1)
   auto fast_tile = [&](const StagePtrs& sp_) __attribute__((always_inline)) {
-    static_assert(NDB == 4 || NDB == 2, "pair schedule below is written for D = 128 (used) and compiles for 64");
-    bf16x8 qn[NKS];
+    static_assert(NDB == 4 || NDB == 2, "the schedule below is written for D = 128 (used) and only has to compile for 64");
+    bf16x8 qn[2][NKS], don[2][NKS];
+    f32x4 l4[2][4];
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], 0);
+    for (int ks = 0; ks < NKS; ++ks) {
+      qn[0][ks] = lds_read8(sp_.nat[ks], 0);
+      don[0][ks] = lds_read8(sp_.nat[ks], TILE_BYTES);
+    }
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) l4[0][q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (8 * q4) * 4);
+    asm_fence();
 #pragma unroll
     for (int rb = 0; rb < NB; ++rb) {
+      const int cur = rb & 1, nxt = cur ^ 1;
       const int blk = 32 * rb * ROW_BYTES;
-      bf16x8 don[NKS];
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) don[ks] = lds_read8(sp_.nat[ks], blk + TILE_BYTES);
-      f32x4 l4[4];
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) l4[q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (32 * rb + 8 * q4) * 4);
-      asm_fence();
+      const bool more = rb + 1 < NB;
       f32x16 s, dp;
-      mfma_first_b_agpr(s, qn[0], kf[0]);
-#pragma unroll
-      for (int ks = 1; ks < NKS; ++ks) mfma_next_b_agpr(s, qn[ks], kf[ks]);
-      asm_fence();
-      bf16x8 dotf[2][NDB];
-#pragma unroll
-      for (int sblk = 0; sblk < 2; ++sblk)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          const int off = blk + 16 * sblk * ROW_BYTES + TILE_BYTES;
-          dotf[sblk][db] = cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
-        }
+      bf16x8 dotf[2][NDB], qtf[2][NDB];
       f32x4 d4[4];
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) d4[q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (BQ + 32 * rb + 8 * q4) * 4);
-      asm_fence();
       float pr[16];
       uint32_t pw[8], dw[8];
       auto p_pair = [&](int g2, auto lead) __attribute__((always_inline)) {
         const int r = 2 * g2;
-        softmax_pair<decltype(lead)::value>(pr[r], pr[r + 1], pw[g2], s[r], s[r + 1], c, l4[r >> 2][r & 3], l4[r >> 2][(r & 3) + 1]);
+        softmax_pair<decltype(lead)::value>(pr[r], pr[r + 1], pw[g2], s[r], s[r + 1], c, l4[cur][r >> 2][r & 3],
+                                            l4[cur][r >> 2][(r & 3) + 1]);
       };
       auto ds_pair = [&](int g2, auto lead) __attribute__((always_inline)) {
         const int r = 2 * g2;
         dscore_pair<decltype(lead)::value>(dw[g2], pr[r], pr[r + 1], dp[r], dp[r + 1], d4[r >> 2][r & 3], d4[r >> 2][(r & 3) + 1]);
       };
-      // dP chain with the probabilities of pairs 0..5 behind MFMAs 2..7
-      mfma_first_b_agpr(dp, don[0], vf[0]);
+      auto tr_frag = [&](int tile_bytes, int m) __attribute__((always_inline)) {  // fragment m = (sblk, db) of a transposed operand
+        const int sblk = m / NDB, db = m % NDB;
+        const int off = blk + 16 * sblk * ROW_BYTES + tile_bytes;
+        return cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
+      };
+      // ---- S chain
 #pragma unroll
-      for (int ks = 1; ks < NKS; ++ks) {
-        mfma_next_b_agpr(dp, don[ks], vf[ks]);
+      for (int ks = 0; ks < NKS; ++ks) {
+        if (ks == 0) mfma_first_b_agpr(s, qn[cur][0], kf[0]);
+        else mfma_next_b_agpr(s, qn[cur][ks], kf[ks]);
+        if (ks < 2 * NDB) dotf[ks / NDB][ks % NDB] = tr_frag(TILE_BYTES, ks);
+        if ((ks & 1) == 0) d4[ks / 2] = *reinterpret_cast<const f32x4*>(sp_.stat + (BQ + 32 * rb + 8 * (ks / 2)) * 4);
+        asm_fence();
+      }
+      // ---- dP chain
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        if (ks == 0) mfma_first_b_agpr(dp, don[cur][0], vf[0]);
+        else mfma_next_b_agpr(dp, don[cur][ks], vf[ks]);
+        if (ks < 2 * NDB) qtf[ks / NDB][ks % NDB] = tr_frag(0, ks);
         if (ks == 2) p_pair(0, std::true_type{});
         if (ks > 2) p_pair(ks - 2, std::false_type{});
+        asm_fence();
       }
-      asm_fence();
-      bf16x8 qtf[2][NDB];
-#pragma unroll
-      for (int sblk = 0; sblk < 2; ++sblk)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          const int off = blk + 16 * sblk * ROW_BYTES;
-          qtf[sblk][db] = cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
-        }
-      asm_fence();
-      // dV chain: P of rows 0-15 is ready; pairs 6,7 follow MFMAs 0,1; dS pairs 0..5 follow MFMAs 2..7
+      // ---- dV chain
       const bf16x8 pf0 = frag_from_words(pw[0], pw[1], pw[2], pw[3]);
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         mfma_acc_agpr(dvacc[db], dotf[0][db], pf0);
+        if (more) qn[nxt][db] = lds_read8(sp_.nat[db], blk + 32 * ROW_BYTES);
         if (db < 2) p_pair(6 + db, std::false_type{});
         if (db == 2) ds_pair(0, std::true_type{});
         if (db == 3) ds_pair(1, std::false_type{});
+        asm_fence();
       }
       const bf16x8 pf1 = frag_from_words(pw[4], pw[5], pw[6], pw[7]);
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         mfma_acc_agpr(dvacc[db], dotf[1][db], pf1);
+        if (more && NDB + db < NKS) qn[nxt][NDB + db] = lds_read8(sp_.nat[NDB + db], blk + 32 * ROW_BYTES);
         ds_pair(2 + db, std::false_type{});
+        asm_fence();
       }
-      asm_fence();
-      // Q rows of the next block ride along with the dK chain
-      if (rb + 1 < NB) {
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], blk + 32 * ROW_BYTES);
-      }
-      asm_fence();
+      // ---- dK chain
       const bf16x8 dsf0 = frag_from_words(dw[0], dw[1], dw[2], dw[3]);
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         mfma_acc_agpr(dkacc[db], qtf[0][db], dsf0);
+        if (more) don[nxt][db] = lds_read8(sp_.nat[db], blk + 32 * ROW_BYTES + TILE_BYTES);
+        if (more) l4[nxt][db] = *reinterpret_cast<const f32x4*>(sp_.stat + (32 * (rb + 1) + 8 * db) * 4);
         if (db < 2) ds_pair(6 + db, std::false_type{});
+        asm_fence();
       }
       const bf16x8 dsf1 = frag_from_words(dw[4], dw[5], dw[6], dw[7]);
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) mfma_acc_agpr(dkacc[db], qtf[1][db], dsf1);
+      for (int db = 0; db < NDB; ++db) {
+        mfma_acc_agpr(dkacc[db], qtf[1][db], dsf1);
+        if (more && NDB + db < NKS) don[nxt][NDB + db] = lds_read8(sp_.nat[NDB + db], blk + 32 * ROW_BYTES + TILE_BYTES);
+        asm_fence();
+      }
     }
   };
 

@@ -317,19 +317,28 @@ struct TileCoord {
   bool valid;
 };
 
-// Tiles of `TS` tokens never straddle documents.  Work item w = blockIdx.x is decoded as
-// head = w % (B*H) and tile = tiles-1 - w / (B*H): consecutive workgroups (which the
-// hardware deals round-robin to the 8 XCDs) belong to different heads, so with B*H a
-// multiple of 8 each head's K/V stream stays inside one XCD's L2; `heavy_last` says
+// Tiles of `TS` tokens never straddle documents.  The hardware deals consecutive workgroups
+// round-robin to the 8 XCDs, each with its own L2.  When B*H is a multiple of 8, XCD x gets the
+// heads x, x+8, ... and walks them one after the other, all tiles of a head before the next
+// head: the workgroups that run together on an XCD then stream the SAME head's K/V (or Q/dO)
+// through its L2 nearly in lock-step, and each is fetched from HBM once per group of
+// co-resident tiles.  Otherwise heads simply alternate (head = w % (B*H)).  `heavy_last` says
 // whether high tile numbers carry the most work (forward and dq: causal rows late in a
-// document see more keys) so that the heaviest tiles are dispatched first.
+// document see more keys) so that the heaviest tiles of a head are dispatched first.
 template <int TS>
 __device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads, bool heavy_last, int* scratch) {
   TileCoord c;
   int nH = (int)p.B * heads;
   int w = blockIdx.x;
-  int hh = w % nH;
-  int t = w / nH;
+  int hh, t;
+  if (nH % 8 == 0) {
+    const int xcd = w & 7, slot = w >> 3;
+    hh = xcd + 8 * (slot / p.tiles);
+    t = slot % p.tiles;
+  } else {
+    hh = w % nH;
+    t = w / nH;
+  }
   if (heavy_last) t = p.tiles - 1 - t;
   c.b = hh / heads;
   c.h = hh % heads;
