@@ -270,40 +270,69 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   ld.init(tid, q_pitch);
   const int wave_u = ld.wave;
 
-  // Asynchronous copy of step `st` (query head, query tile) into stage `slot`.
-  auto issue_step = [&](const int st, const int slot) __attribute__((always_inline)) {
-    const int hq = g * group + st / nqt;
-    const int i0 = (st % nqt) * BQ;  // first row of the tile, relative to q_begin
-    const int rows = nq - i0;        // valid rows (>= 1)
+  // Asynchronous copy of one (query head, query tile) into a stage.  The tile is described once
+  // (scalar arithmetic only) and then copied either all at once or piece by piece: a wave issues
+  // in order, and 17 back-to-back copy instructions hold it for as long as the memory pipeline
+  // needs to accept them (about 1 KiB per 16 cycles per CU), so the hand-sequenced tile spreads
+  // them between its MFMA chains.
+  struct TileCopy {
+    const char* qg;    // first row of the Q tile of that head
+    const char* dog;   // first row of the dO tile
+    const char* stat;  // lse*log2e (waves 0,1) or delta (waves 2,3) of the tile's first row
+    int rows;          // valid rows, >= 1
+    uint32_t base;     // LDS address of the stage
+  };
+  constexpr int kPieces = 2 * (BQ / 64) * AsyncTile<D>::NI + 1;
+  auto describe = [&](const int hq_idx, const int tile_idx, const int slot) __attribute__((always_inline)) {
+    TileCopy t;
+    const int hq = g * group + hq_idx;
+    const int i0 = tile_idx * BQ;  // first row of the tile, relative to q_begin
+    t.rows = nq - i0;
     const int64_t tok = (int64_t)tc.b * p.S + q_begin + i0;
-    const char* qg = reinterpret_cast<const char*>(p.q + (tok * p.Hq + hq) * D);
-    const char* dog = reinterpret_cast<const char*>(p.dout + (tok * p.Hq + hq) * D);
-    const uint32_t base = lds0 + slot * STAGE_BYTES;
+    t.qg = reinterpret_cast<const char*>(p.q + (tok * p.Hq + hq) * D);
+    t.dog = reinterpret_cast<const char*>(p.dout + (tok * p.Hq + hq) * D);
+    const int64_t idx = ((int64_t)tc.b * p.Hq + hq) * p.S + q_begin + i0;
+    t.stat = reinterpret_cast<const char*>((wave_u < 2 ? p.lse2 : p.delta) + idx);
+    t.base = lds0 + slot * STAGE_BYTES;
+    return t;
+  };
+  // statistics, one dword per lane = one row: waves 0,1 copy lse*log2e of rows 0-63, 64-127;
+  // waves 2,3 copy delta.  Rows past the end repeat the last valid row (masked later).
+  auto copy_stats = [&](const TileCopy& t) __attribute__((always_inline)) {
+    const int half = wave_u & 1;
+    int r = 64 * half + lane;
+    r = r < t.rows ? r : t.rows - 1;
+    const char* src = uniform(t.stat);
+    const uint32_t dst = uniform(t.base + 2 * TILE_BYTES + (wave_u < 2 ? 0 : BQ * 4) + half * 256);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"((uint32_t)r * 4u), "s"(src), "s"(dst)
+                 : "memory");
+  };
+  auto copy_all = [&](const TileCopy& t) __attribute__((always_inline)) {
 #pragma unroll
     for (int part = 0; part < BQ / 64; ++part) {
-      // rows past the end repeat the last valid row (masked later); a part that lies entirely
-      // past the end repeats it 64 times
-      const int first = rows > 64 * part ? 64 * part : rows - 1;
-      const int valid = rows > 64 * part ? rows - 64 * part : 1;
-      ld.load(base + part * 64 * ROW_BYTES, qg + (int64_t)first * q_pitch, valid);
-      ld.load(base + TILE_BYTES + part * 64 * ROW_BYTES, dog + (int64_t)first * q_pitch, valid);
+      // a part that lies entirely past the end repeats the last valid row 64 times
+      const int first = t.rows > 64 * part ? 64 * part : t.rows - 1;
+      const int valid = t.rows > 64 * part ? t.rows - 64 * part : 1;
+      ld.load(t.base + part * 64 * ROW_BYTES, t.qg + (int64_t)first * q_pitch, valid);
+      ld.load(t.base + TILE_BYTES + part * 64 * ROW_BYTES, t.dog + (int64_t)first * q_pitch, valid);
     }
-    // statistics, one dword per lane = one row: waves 0,1 copy lse*log2e of rows 0-63, 64-127;
-    // waves 2,3 copy delta
-    {
-      const int half = wave_u & 1;
-      int r = 64 * half + lane;
-      r = r < rows ? r : rows - 1;
-      const int64_t idx = ((int64_t)tc.b * p.Hq + hq) * p.S + q_begin + i0;
-      const char* src = uniform(reinterpret_cast<const char*>((wave_u < 2 ? p.lse2 : p.delta) + idx));
-      const uint32_t dst = uniform(base + 2 * TILE_BYTES + (wave_u < 2 ? 0 : BQ * 4) + half * 256);
-      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                   :
-                   : "v"((uint32_t)r * 4u), "s"(src), "s"(dst)
-                   : "memory");
+    copy_stats(t);
+  };
+  // piece k of a tile that is known to have all BQ rows
+  auto copy_piece = [&](const TileCopy& t, const int k) __attribute__((always_inline)) {
+    constexpr int NI = AsyncTile<D>::NI, RPI = AsyncTile<D>::RPI;
+    if (k == kPieces - 1) {
+      copy_stats(t);
+    } else {
+      const int tensor = k / ((BQ / 64) * NI), part = (k / NI) % (BQ / 64), i = k % NI;
+      const int row = 64 * part + 4 * RPI * i;
+      async_copy16(ld.voff, (tensor ? t.dog : t.qg) + (int64_t)row * q_pitch,
+                   t.base + tensor * TILE_BYTES + part * 64 * ROW_BYTES + (i * 4 + wave_u) * 1024);
     }
   };
-  issue_step(0, 0);
+  copy_all(describe(0, 0, 0));
 
   // This lane's key (column of S); clamped copies are computed but never written.
   int64_t key = k0 + wv * 32 + n;
@@ -356,7 +385,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   //   dP      M8-15  dP = dO V^T    P pairs 0..5 from M10           Q^T (b)
   //   dV      M16-23 dV += dO^T P   P pairs 6,7; dS pairs 0..5      Q rows (b+1)
   //   dK      M24-31 dK += Q^T dS   dS pairs 6,7                    dO rows (b+1), lse (b+1)
-  auto fast_tile = [&](const StagePtrs& sp_) __attribute__((always_inline)) {
+  auto fast_tile = [&](const StagePtrs& sp_, const TileCopy& next, auto spread_copies) __attribute__((always_inline)) {
+    constexpr bool kSpread = decltype(spread_copies)::value;  // copy the next tile piece by piece between the chains
     static_assert(NDB == 4 || NDB == 2, "the schedule below is written for D = 128 (used) and only has to compile for 64");
     bf16x8 qn[2][NKS], don[2][NKS];
     f32x4 l4[2][4];
@@ -392,31 +422,58 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
         const int off = blk + 16 * sblk * ROW_BYTES + tile_bytes;
         return cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
       };
+      auto spread = [&](int chain) __attribute__((always_inline)) {   // chain 0..3 of this block
+        if (kSpread) {
+          // 4 * NB chain slots per tile, kPieces pieces: one per slot, the surplus doubled up in the first slots
+          const int slot_idx = 4 * rb + chain;
+          if (slot_idx < kPieces) copy_piece(next, slot_idx);
+          if (slot_idx + 4 * NB < kPieces) copy_piece(next, slot_idx + 4 * NB);
+        }
+      };
       // ---- S chain
+      spread(0);
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         if (ks == 0) mfma_first_b_agpr(s, qn[cur][0], kf[0]);
         else mfma_next_b_agpr(s, qn[cur][ks], kf[ks]);
+#ifdef IE_EXP_DKDV_NOTR
+        if (ks < 2 * NDB) dotf[ks / NDB][ks % NDB] = don[cur][ks];
+#else
         if (ks < 2 * NDB) dotf[ks / NDB][ks % NDB] = tr_frag(TILE_BYTES, ks);
+#endif
+#ifdef IE_EXP_DKDV_NOSTAT
+        if ((ks & 1) == 0) d4[ks / 2] = l4[cur][ks / 2];
+#else
         if ((ks & 1) == 0) d4[ks / 2] = *reinterpret_cast<const f32x4*>(sp_.stat + (BQ + 32 * rb + 8 * (ks / 2)) * 4);
+#endif
         asm_fence();
       }
       // ---- dP chain
+      spread(1);
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         if (ks == 0) mfma_first_b_agpr(dp, don[cur][0], vf[0]);
         else mfma_next_b_agpr(dp, don[cur][ks], vf[ks]);
+#ifdef IE_EXP_DKDV_NOTR
+        if (ks < 2 * NDB) qtf[ks / NDB][ks % NDB] = qn[cur][ks];
+#else
         if (ks < 2 * NDB) qtf[ks / NDB][ks % NDB] = tr_frag(0, ks);
+#endif
         if (ks == 2) p_pair(0, std::true_type{});
         if (ks > 2) p_pair(ks - 2, std::false_type{});
         asm_fence();
       }
       // ---- dV chain
+      spread(2);
       const bf16x8 pf0 = frag_from_words(pw[0], pw[1], pw[2], pw[3]);
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         mfma_acc_agpr(dvacc[db], dotf[0][db], pf0);
+#ifdef IE_EXP_DKDV_NONAT
+        if (more) qn[nxt][db] = qn[cur][db];
+#else
         if (more) qn[nxt][db] = lds_read8(sp_.nat[db], blk + 32 * ROW_BYTES);
+#endif
         if (db < 2) p_pair(6 + db, std::false_type{});
         if (db == 2) ds_pair(0, std::true_type{});
         if (db == 3) ds_pair(1, std::false_type{});
@@ -426,17 +483,30 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         mfma_acc_agpr(dvacc[db], dotf[1][db], pf1);
+#ifdef IE_EXP_DKDV_NONAT
+        if (more && NDB + db < NKS) qn[nxt][NDB + db] = qn[cur][NDB + db];
+#else
         if (more && NDB + db < NKS) qn[nxt][NDB + db] = lds_read8(sp_.nat[NDB + db], blk + 32 * ROW_BYTES);
+#endif
         ds_pair(2 + db, std::false_type{});
         asm_fence();
       }
       // ---- dK chain
+      spread(3);
       const bf16x8 dsf0 = frag_from_words(dw[0], dw[1], dw[2], dw[3]);
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         mfma_acc_agpr(dkacc[db], qtf[0][db], dsf0);
+#ifdef IE_EXP_DKDV_NONAT
+        if (more) don[nxt][db] = don[cur][db];
+#else
         if (more) don[nxt][db] = lds_read8(sp_.nat[db], blk + 32 * ROW_BYTES + TILE_BYTES);
+#endif
+#ifdef IE_EXP_DKDV_NOSTAT
+        if (more) l4[nxt][db] = l4[cur][db];
+#else
         if (more) l4[nxt][db] = *reinterpret_cast<const f32x4*>(sp_.stat + (32 * (rb + 1) + 8 * db) * 4);
+#endif
         if (db < 2) ds_pair(6 + db, std::false_type{});
         asm_fence();
       }
@@ -444,7 +514,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         mfma_acc_agpr(dkacc[db], qtf[1][db], dsf1);
+#ifdef IE_EXP_DKDV_NONAT
+        if (more && NDB + db < NKS) don[nxt][NDB + db] = don[cur][NDB + db];
+#else
         if (more && NDB + db < NKS) don[nxt][NDB + db] = lds_read8(sp_.nat[NDB + db], blk + 32 * ROW_BYTES + TILE_BYTES);
+#endif
         asm_fence();
       }
     }
@@ -541,17 +615,44 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     }
   };
 
+#ifdef IE_EXP_TIMING
+  uint64_t t_fast = 0, t_gen = 0, t_sync = 0, n_fast = 0;
+  const uint64_t t_begin = __builtin_readcyclecounter();
+#endif
   // One step = one query tile of one query head.  `slot` (compile-time) is the stage that holds it.
+  int hq_idx = 0, tile_idx = 0;  // the step being computed
   auto step_fn = [&](const int st, auto slot_c) __attribute__((always_inline)) {
     constexpr int slot = decltype(slot_c)::value;
-    if (st + 1 < total) issue_step(st + 1, 1 - slot);
-    const int i0 = (st % nqt) * BQ;
+    int next_hq = hq_idx, next_tile = tile_idx + 1;
+    if (next_tile == nqt) { next_tile = 0; ++next_hq; }
+    const bool has_next = st + 1 < total;
+    const TileCopy next = describe(has_next ? next_hq : hq_idx, has_next ? next_tile : tile_idx, 1 - slot);
+    const bool next_full = has_next && next.rows >= BQ;
+    const int i0 = tile_idx * BQ;
     // Mask when a key of this wave can exceed a row of the tile (causal) or rows run past the document.
     const bool need_mask = (p.causal && wv * 32 + 31 > i0) || (i0 + BQ > nq);
-    if (D == 128 && !need_mask) fast_tile(sp[slot]);
-    else generic_tile(sp[slot], i0);
+    const bool fast = D == 128 && !need_mask;
+#ifdef IE_EXP_TIMING
+    const uint64_t tt0 = __builtin_readcyclecounter();
+#endif
+    if (fast && next_full) {
+      fast_tile(sp[slot], next, std::true_type{});
+    } else {
+      if (has_next) copy_all(next);
+      if (fast) fast_tile(sp[slot], next, std::false_type{});
+      else generic_tile(sp[slot], i0);
+    }
+#ifdef IE_EXP_TIMING
+    const uint64_t tt1 = __builtin_readcyclecounter();
+    if (fast) { t_fast += tt1 - tt0; n_fast += 1; } else { t_gen += tt1 - tt0; }
+#endif
     async_wait_all();
     __syncthreads();
+#ifdef IE_EXP_TIMING
+    t_sync += __builtin_readcyclecounter() - tt1;
+#endif
+    hq_idx = next_hq;
+    tile_idx = next_tile;
   };
 
   agpr_loads_wait();  // K/V fragments (and the first stage's copies) have arrived
@@ -564,6 +665,13 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   }
   if (st < total) step_fn(st, std::integral_constant<int, 0>{});
   mfma_result_fence();  // the last assembly MFMAs have retired before the accumulators are read
+#ifdef IE_EXP_TIMING
+  if (tid == 0) {
+    uint64_t* dbg = reinterpret_cast<uint64_t*>(p.dq) + (size_t)blockIdx.x * 8;
+    dbg[0] = __builtin_readcyclecounter() - t_begin; dbg[1] = t_fast; dbg[2] = n_fast; dbg[3] = t_gen; dbg[4] = t_sync; dbg[5] = total;
+    dbg[6] = t_begin; dbg[7] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));  // HW_ID
+  }
+#endif
 
   if (key_ok) {
     __bf16* dkrow = p.dk + kvhead + key * kv_stride;
