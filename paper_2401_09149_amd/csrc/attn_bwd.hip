@@ -374,154 +374,130 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 
   const float c = p.scale_log2;
 
-  // Unmasked tile, hand-sequenced (see mfma_asm.hpp).  Per 32-row block the 32 MFMAs run back
-  // to back; the elementwise work rides in their shadow at least two MFMAs behind the chain
-  // whose result it needs, and the LDS reads are spread one or two per MFMA instead of being
-  // issued in bursts (a wave issues in order: a burst of 32 reads holds back the MFMAs behind
-  // it for as long as the LDS pipe needs to drain them).  Every operand group is requested two
-  // chains before the chain that consumes it:
-  //   chain   MFMAs                 VALU in the shadow              LDS reads issued
-  //   S       M0-7   S  = Q K^T                                     dO^T (block b), delta (b)
-  //   dP      M8-15  dP = dO V^T    P pairs 0..5 from M10           Q^T (b)
-  //   dV      M16-23 dV += dO^T P   P pairs 6,7; dS pairs 0..5      Q rows (b+1)
-  //   dK      M24-31 dK += Q^T dS   dS pairs 6,7                    dO rows (b+1), lse (b+1)
+  // Unmasked tile, hand-sequenced (see mfma_asm.hpp).  The MFMA pipe is the scarce resource and
+  // the issue port is shared: an MFMA holds it for about 16 of its 32 cycles, which leaves room
+  // for about four ordinary VALU instructions per MFMA (v_exp_f32 counts twice).  A block's
+  // elementwise work is 16 x (fma, exp) + 8 packs for P and 16 x (sub, mul) + 8 packs for dS,
+  // about three slots per MFMA when it is spread over all 32 MFMAs of a block - which needs the
+  // chains of neighbouring blocks to be interleaved, because P can only start after S and dS
+  // only after dP.  Steady state for block b (four chains of 8 MFMAs):
+  //   A  dP(b)   = dO V^T      + P elements 0..6 of block b          LDS: dO^T(b), delta(b)
+  //   B  dK(b-1) += Q^T dS     + P elements 7..14                    LDS: Q rows(b+1)
+  //   C  dV(b)   += dO^T P     + P element 15, dS elements 0..6      LDS: Q^T(b), lse(b+1)
+  //   D  S(b+1)  = Q K^T       + dS elements 7..15                   LDS: dO rows(b+1)
+  // Every operand group is requested at least one chain before the chain that consumes it and
+  // one or two reads per MFMA, never in a burst (a wave issues in order).  The first block of a
+  // tile has no dK in B and the last no S in D; the pipeline is drained at the end of the tile.
   auto fast_tile = [&](const StagePtrs& sp_, const TileCopy& next, auto spread_copies) __attribute__((always_inline)) {
     constexpr bool kSpread = decltype(spread_copies)::value;  // copy the next tile piece by piece between the chains
     static_assert(NDB == 4 || NDB == 2, "the schedule below is written for D = 128 (used) and only has to compile for 64");
-    bf16x8 qn[2][NKS], don[2][NKS];
-    f32x4 l4[2][4];
+    bf16x8 qn[NKS], don[NKS], dotf[2][NDB], qtf[2][NDB];
+    f32x4 l4[4], d4[4];
+    f32x16 s, dp;
+    float pr[16], ds[16];
+    uint32_t pw[8], dw[8];
+    bf16x8 dsf0, dsf1;
+
+    auto tr_frag = [&](int blk, int tile_bytes, int m) __attribute__((always_inline)) {  // fragment m = (sblk, db)
+      const int sblk = m / NDB, db = m % NDB;
+      const int off = blk + 16 * sblk * ROW_BYTES + tile_bytes;
+      return cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
+    };
+    auto p_elem = [&](int e, auto lead) __attribute__((always_inline)) {
+      if (e >= 2 && (e & 1) == 0) pack_pair(pw[e / 2 - 1], pr[e - 2], pr[e - 1]);  // previous pair, one MFMA after its last exp
+      softmax_elem<decltype(lead)::value>(pr[e], s[e], c, l4[e >> 2][e & 3]);
+    };
+    auto ds_elem = [&](int e) __attribute__((always_inline)) {
+      dscore_elem(ds[e], pr[e], dp[e], d4[e >> 2][e & 3]);
+      if (e & 1) pack_pair(dw[e / 2], ds[e - 1], ds[e]);
+    };
+    auto spread = [&](int slot_idx) __attribute__((always_inline)) {   // 4 * NB chain slots per tile
+      if (kSpread) {
+        if (slot_idx < kPieces) copy_piece(next, slot_idx);
+        if (slot_idx + 4 * NB < kPieces) copy_piece(next, slot_idx + 4 * NB);
+      }
+    };
+
+    // prologue: operands of block 0 (latency exposed once per tile), then S(0)
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      qn[0][ks] = lds_read8(sp_.nat[ks], 0);
-      don[0][ks] = lds_read8(sp_.nat[ks], TILE_BYTES);
-    }
+    for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], 0);
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) l4[0][q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (8 * q4) * 4);
+    for (int ks = 0; ks < NKS; ++ks) don[ks] = lds_read8(sp_.nat[ks], TILE_BYTES);
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) l4[q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (8 * q4) * 4);
     asm_fence();
 #pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      if (ks == 0) mfma_first_b_agpr(s, qn[0], kf[0]);
+      else mfma_next_b_agpr(s, qn[ks], kf[ks]);
+    }
+    asm_fence();
+
+#pragma unroll
     for (int rb = 0; rb < NB; ++rb) {
-      const int cur = rb & 1, nxt = cur ^ 1;
       const int blk = 32 * rb * ROW_BYTES;
       const bool more = rb + 1 < NB;
-      f32x16 s, dp;
-      bf16x8 dotf[2][NDB], qtf[2][NDB];
-      f32x4 d4[4];
-      float pr[16];
-      uint32_t pw[8], dw[8];
-      auto p_pair = [&](int g2, auto lead) __attribute__((always_inline)) {
-        const int r = 2 * g2;
-        softmax_pair<decltype(lead)::value>(pr[r], pr[r + 1], pw[g2], s[r], s[r + 1], c, l4[cur][r >> 2][r & 3],
-                                            l4[cur][r >> 2][(r & 3) + 1]);
-      };
-      auto ds_pair = [&](int g2, auto lead) __attribute__((always_inline)) {
-        const int r = 2 * g2;
-        dscore_pair<decltype(lead)::value>(dw[g2], pr[r], pr[r + 1], dp[r], dp[r + 1], d4[r >> 2][r & 3], d4[r >> 2][(r & 3) + 1]);
-      };
-      auto tr_frag = [&](int tile_bytes, int m) __attribute__((always_inline)) {  // fragment m = (sblk, db) of a transposed operand
-        const int sblk = m / NDB, db = m % NDB;
-        const int off = blk + 16 * sblk * ROW_BYTES + tile_bytes;
-        return cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
-      };
-      auto spread = [&](int chain) __attribute__((always_inline)) {   // chain 0..3 of this block
-        if (kSpread) {
-          // 4 * NB chain slots per tile, kPieces pieces: one per slot, the surplus doubled up in the first slots
-          const int slot_idx = 4 * rb + chain;
-          if (slot_idx < kPieces) copy_piece(next, slot_idx);
-          if (slot_idx + 4 * NB < kPieces) copy_piece(next, slot_idx + 4 * NB);
-        }
-      };
-      // ---- S chain
-      spread(0);
+      // ---- A: dP(b) with P elements 0..6; reads dO^T(b) and delta(b)
+      spread(4 * rb + 0);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        if (ks == 0) mfma_first_b_agpr(s, qn[cur][0], kf[0]);
-        else mfma_next_b_agpr(s, qn[cur][ks], kf[ks]);
-#ifdef IE_EXP_DKDV_NOTR
-        if (ks < 2 * NDB) dotf[ks / NDB][ks % NDB] = don[cur][ks];
-#else
-        if (ks < 2 * NDB) dotf[ks / NDB][ks % NDB] = tr_frag(TILE_BYTES, ks);
-#endif
-#ifdef IE_EXP_DKDV_NOSTAT
-        if ((ks & 1) == 0) d4[ks / 2] = l4[cur][ks / 2];
-#else
-        if ((ks & 1) == 0) d4[ks / 2] = *reinterpret_cast<const f32x4*>(sp_.stat + (BQ + 32 * rb + 8 * (ks / 2)) * 4);
-#endif
+      for (int m = 0; m < NKS; ++m) {
+        if (m == 0) mfma_first_b_agpr(dp, don[0], vf[0]);
+        else mfma_next_b_agpr(dp, don[m], vf[m]);
+        if (m < 2 * NDB) dotf[m / NDB][m % NDB] = tr_frag(blk, TILE_BYTES, m);
+        if ((m & 1) == 0) d4[m / 2] = *reinterpret_cast<const f32x4*>(sp_.stat + (BQ + 32 * rb + 8 * (m / 2)) * 4);
+        if (m == 1) p_elem(0, std::true_type{});
+        if (m > 1) p_elem(m - 1, std::false_type{});
         asm_fence();
       }
-      // ---- dP chain
-      spread(1);
+      // ---- B: dK(b-1) with P elements 7..14; reads the Q rows of block b+1
+      spread(4 * rb + 1);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        if (ks == 0) mfma_first_b_agpr(dp, don[cur][0], vf[0]);
-        else mfma_next_b_agpr(dp, don[cur][ks], vf[ks]);
-#ifdef IE_EXP_DKDV_NOTR
-        if (ks < 2 * NDB) qtf[ks / NDB][ks % NDB] = qn[cur][ks];
-#else
-        if (ks < 2 * NDB) qtf[ks / NDB][ks % NDB] = tr_frag(0, ks);
-#endif
-        if (ks == 2) p_pair(0, std::true_type{});
-        if (ks > 2) p_pair(ks - 2, std::false_type{});
+      for (int m = 0; m < 2 * NDB; ++m) {
+        if (rb > 0) mfma_acc_agpr(dkacc[m % NDB], qtf[m / NDB][m % NDB], m < NDB ? dsf0 : dsf1);
+        if (more && m < NKS) qn[m] = lds_read8(sp_.nat[m], blk + 32 * ROW_BYTES);
+        p_elem(7 + m, std::false_type{});
         asm_fence();
       }
-      // ---- dV chain
-      spread(2);
+      // ---- C: dV(b) with P element 15 and dS elements 0..6; reads Q^T(b) and lse(b+1)
+      spread(4 * rb + 2);
       const bf16x8 pf0 = frag_from_words(pw[0], pw[1], pw[2], pw[3]);
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        mfma_acc_agpr(dvacc[db], dotf[0][db], pf0);
-#ifdef IE_EXP_DKDV_NONAT
-        if (more) qn[nxt][db] = qn[cur][db];
-#else
-        if (more) qn[nxt][db] = lds_read8(sp_.nat[db], blk + 32 * ROW_BYTES);
-#endif
-        if (db < 2) p_pair(6 + db, std::false_type{});
-        if (db == 2) ds_pair(0, std::true_type{});
-        if (db == 3) ds_pair(1, std::false_type{});
+      for (int m = 0; m < NDB; ++m) {
+        mfma_acc_agpr(dvacc[m], dotf[0][m], pf0);
+        qtf[0][m] = tr_frag(blk, 0, m);
+        if (m == 0) softmax_elem<false>(pr[15], s[15], c, l4[3][3]);
+        if (m == 1) pack_pair(pw[7], pr[14], pr[15]);
+        if (m >= 1) ds_elem(m - 1);
         asm_fence();
       }
       const bf16x8 pf1 = frag_from_words(pw[4], pw[5], pw[6], pw[7]);
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        mfma_acc_agpr(dvacc[db], dotf[1][db], pf1);
-#ifdef IE_EXP_DKDV_NONAT
-        if (more && NDB + db < NKS) qn[nxt][NDB + db] = qn[cur][NDB + db];
-#else
-        if (more && NDB + db < NKS) qn[nxt][NDB + db] = lds_read8(sp_.nat[NDB + db], blk + 32 * ROW_BYTES);
-#endif
-        ds_pair(2 + db, std::false_type{});
+      for (int m = 0; m < NDB; ++m) {
+        mfma_acc_agpr(dvacc[m], dotf[1][m], pf1);
+        qtf[1][m] = tr_frag(blk, 0, NDB + m);
+        if (more) l4[m] = *reinterpret_cast<const f32x4*>(sp_.stat + (32 * (rb + 1) + 8 * m) * 4);
+        ds_elem(NDB - 1 + m);
         asm_fence();
       }
-      // ---- dK chain
-      spread(3);
-      const bf16x8 dsf0 = frag_from_words(dw[0], dw[1], dw[2], dw[3]);
+      // ---- D: S(b+1) with dS elements 7..15; reads the dO rows of block b+1
+      spread(4 * rb + 3);
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        mfma_acc_agpr(dkacc[db], qtf[0][db], dsf0);
-#ifdef IE_EXP_DKDV_NONAT
-        if (more) don[nxt][db] = don[cur][db];
-#else
-        if (more) don[nxt][db] = lds_read8(sp_.nat[db], blk + 32 * ROW_BYTES + TILE_BYTES);
-#endif
-#ifdef IE_EXP_DKDV_NOSTAT
-        if (more) l4[nxt][db] = l4[cur][db];
-#else
-        if (more) l4[nxt][db] = *reinterpret_cast<const f32x4*>(sp_.stat + (32 * (rb + 1) + 8 * db) * 4);
-#endif
-        if (db < 2) ds_pair(6 + db, std::false_type{});
+      for (int m = 0; m < NKS; ++m) {
+        if (more) {
+          if (m == 0) mfma_first_b_agpr(s, qn[0], kf[0]);
+          else mfma_next_b_agpr(s, qn[m], kf[m]);
+          don[m] = lds_read8(sp_.nat[m], blk + 32 * ROW_BYTES + TILE_BYTES);
+        }
+        ds_elem(2 * NDB - 1 + m);
+        if (m == NKS - 1) ds_elem(2 * NDB - 1 + NKS);
         asm_fence();
       }
-      const bf16x8 dsf1 = frag_from_words(dw[4], dw[5], dw[6], dw[7]);
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        mfma_acc_agpr(dkacc[db], qtf[1][db], dsf1);
-#ifdef IE_EXP_DKDV_NONAT
-        if (more && NDB + db < NKS) don[nxt][NDB + db] = don[cur][NDB + db];
-#else
-        if (more && NDB + db < NKS) don[nxt][NDB + db] = lds_read8(sp_.nat[NDB + db], blk + 32 * ROW_BYTES + TILE_BYTES);
-#endif
-        asm_fence();
-      }
+      dsf0 = frag_from_words(dw[0], dw[1], dw[2], dw[3]);
+      dsf1 = frag_from_words(dw[4], dw[5], dw[6], dw[7]);
     }
+    // drain: dK of the last block
+#pragma unroll
+    for (int m = 0; m < 2 * NDB; ++m) mfma_acc_agpr(dkacc[m % NDB], qtf[m / NDB][m % NDB], m < NDB ? dsf0 : dsf1);
   };
 
   // Generic tile (diagonal, document end, D = 64): compiler-scheduled, with masks.

@@ -269,8 +269,12 @@ struct AsyncTile {
   // Copies 64 full rows starting at `g` (wave-uniform) into the LDS tile at byte address `lds`.
   __device__ __forceinline__ void load_full(uint32_t lds, const char* g) const {
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
-      async_copy16(voff, g + (uint64_t)(4 * RPI * i) * pitch, lds + (i * 4 + wave) * 1024);
+    for (int i = 0; i < NI; ++i) load_full_piece(lds, g, i);
+  }
+  // One of the NI instructions of load_full, for callers that spread them over their arithmetic
+  // (a wave issues in order, and the memory pipeline accepts about 1 KiB per 16 cycles per CU).
+  __device__ __forceinline__ void load_full_piece(uint32_t lds, const char* g, int i) const {
+    async_copy16(voff, g + (uint64_t)(4 * RPI * i) * pitch, lds + (i * 4 + wave) * 1024);
   }
   // Same when only rows [0, rows_valid) exist: later rows repeat row rows_valid-1 so that no
   // load leaves the tensor (their values are masked by the caller).  1 <= rows_valid <= 64.

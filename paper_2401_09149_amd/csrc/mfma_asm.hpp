@@ -64,6 +64,23 @@ __device__ __forceinline__ void dscore_pair(uint32_t& packed, float p0, float p1
       : "v"(p0), "v"(p1), "v"(dp0), "v"(dp1), "v"(d0), "v"(d1));
 }
 
+// Single-element forms, for schedules that give every MFMA at most ~4 VALU slots.
+// p = exp2(s*c - l).  LEAD: the first use of an MFMA chain's result (see file header).
+template <bool LEAD>
+__device__ __forceinline__ void softmax_elem(float& p, float s, float c, float l) {
+  if (LEAD) asm volatile("s_nop 9");
+  asm volatile("v_fma_f32 %0, %1, %2, -%3\n\tv_exp_f32 %0, %0" : "=&v"(p) : "v"(s), "s"(c), "v"(l));
+}
+// d = p * (dp - delta)
+__device__ __forceinline__ void dscore_elem(float& d, float p, float dp, float delta) {
+  asm volatile("v_sub_f32 %0, %2, %3\n\tv_mul_f32 %0, %0, %1" : "=&v"(d) : "v"(p), "v"(dp), "v"(delta));
+}
+// packed = {bf16(a), bf16(b)}.  When a or b comes from v_exp_f32, at least one other instruction
+// must have been issued since (the callers put an MFMA in between).
+__device__ __forceinline__ void pack_pair(uint32_t& packed, float a, float b) {
+  asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(packed) : "v"(a), "v"(b));
+}
+
 __device__ __forceinline__ bf16x8 frag_from_words(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
   u32x4 w = {a, b, c, d};
   return __builtin_bit_cast(bf16x8, w);
