@@ -38,6 +38,11 @@ def build(verbose=False, extra=()):
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    # A kernel whose host stub was not emitted shows up only as a lazily bound undefined symbol.
+    r = subprocess.run(["nm", "-D", "--undefined-only", LIB], capture_output=True, text=True)
+    missing = [l.split()[-1] for l in r.stdout.splitlines() if "_ZN2ie" in l]
+    if missing:
+        raise RuntimeError("libie_attn.so has undefined symbols of its own namespace: " + ", ".join(missing))
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-o", PEAK_PROBE, os.path.join(CSRC, "mfma_peak_probe.hip")],
                        capture_output=True, text=True)
     if r.returncode != 0:

@@ -24,8 +24,9 @@ namespace ie {
 // One (batch, token, head) row of D bf16 per group of D/8 lanes; rows are walked so that
 // consecutive groups take consecutive tokens of one head, which makes the [B,Hq,S]
 // writes contiguous while every read is a full row (D*2 contiguous bytes).  The same pass
-// stores lse * log2(e) next to delta, so that the main kernels can exponentiate with exp2
-// without a per-element rescale.
+// stores lse * log2(e) next to delta.  Both are stored NEGATED: -delta is the C operand of the
+// first MFMA of every dP chain, which then delivers dP - delta directly, and -lse*log2(e) is the
+// addend of the fused multiply-add in front of each exp2.
 template <int D>
 __global__ __launch_bounds__(kThreads) void attn_bwd_delta_kernel(AttnParams p) {
   constexpr int LPR = D / 8;               // lanes per row
@@ -51,8 +52,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_delta_kernel(AttnParams p) 
 #pragma unroll
     for (int s = LPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s, 64);
     if (sub == 0 && i < p.S) {
-      p.delta[hh * p.S + i] = acc;
-      p.lse2[hh * p.S + i] = p.lse[hh * p.S + i] * kLog2e;
+      p.delta[hh * p.S + i] = -acc;
+      p.lse2[hh * p.S + i] = -p.lse[hh * p.S + i] * kLog2e;
     }
   }
 }
@@ -110,8 +111,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
     dof[ks] = *reinterpret_cast<const bf16x8*>(p.dout + qhead + row * q_stride + ks * 16 + h * 8);
   }
   const int64_t stat = ((int64_t)tc.b * p.Hq + tc.h) * p.S + row;
-  const float lse2 = p.lse2[stat];
-  const float delta = p.delta[stat];
+  const float nlse2 = p.lse2[stat];    // -lse * log2(e) of this lane's query
+  const float ndelta = p.delta[stat];  // -delta
 
   const char* nat_ptr[NKS];  // row n of a tile, chunk 2ks + h (A operand: K or V rows)
 #pragma unroll
@@ -124,7 +125,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
     tr_ptr8[db] = smem + tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
   }
 
+  // The dP chain starts from -delta (the same value in all 16 rows: one query per lane), so it
+  // delivers dP - delta.
   const float c = p.scale_log2;
+  f32x16 dp_init;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) dp_init[r] = ndelta;
   f32x16 acc[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
@@ -151,20 +157,22 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
       const int blk = stage + 32 * j * ROW_BYTES;
       f32x16 s, dp;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) s = mfma32(lds_read8(nat_ptr[ks], blk), qf[ks], s);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) dp = mfma32(lds_read8(nat_ptr[ks], blk + TILE_BYTES), dof[ks], dp);
-      // K^T fragments for the dQ product: requested before the elementwise work
+      for (int ks = 0; ks < NKS; ++ks) dp = mfma32(lds_read8(nat_ptr[ks], blk + TILE_BYTES), dof[ks], ks == 0 ? dp_init : dp);
+      // K^T fragments for the dQ product: the first 16 keys' are requested before the
+      // elementwise work, the other 16 keys' while the first half of dS is being formed
       bf16x8 ktf[2][NDB];
-#pragma unroll
-      for (int sblk = 0; sblk < 2; ++sblk)
+      auto load_ktf = [&](int sblk) __attribute__((always_inline)) {
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const int off = blk + 16 * sblk * ROW_BYTES;
           ktf[sblk][db] = cat4(lds_read_tr4(tr_ptr0[db] + off), lds_read_tr4(tr_ptr8[db] + off));
         }
+      };
+      load_ktf(0);
       if (need_mask) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
@@ -173,13 +181,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
       bf16x8 dsf[2];
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk) {
+        if (sblk == 1) load_ktf(1);
         bf16x2 pr[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int r = 8 * sblk + 2 * t;
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], c, -lse2));
-          pr[t] = pack_bf16(p0 * (dp[r] - delta), p1 * (dp[r + 1] - delta));
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, nlse2));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], c, nlse2));
+          pr[t] = pack_bf16(p0 * dp[r], p1 * dp[r + 1]);
         }
         dsf[sblk] = cat_pairs(pr[0], pr[1], pr[2], pr[3]);
       }
@@ -195,8 +204,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
 
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) { consume(qf[ks]); consume(dof[ks]); }
-  consume(lse2);
-  consume(delta);
+  consume(nlse2);
+  consume(ndelta);
   async_wait_all();
   __syncthreads();
   int kt = 0;
@@ -372,59 +381,77 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
 
+  // The dK product of a tile's last 32-row block is left pending when the tile ends and is issued
+  // at the start of the next tile, where it covers the latency of that tile's first LDS reads.
+  bf16x8 qtf[2][NDB];   // Q^T fragments of the block whose dK product comes next
+  bf16x8 dsf0, dsf1;    // its dS fragments
+  bool pending = false; // wave-uniform
+  auto flush_pending = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int m = 0; m < 2 * NDB; ++m) mfma_acc_agpr(dkacc[m % NDB], qtf[m / NDB][m % NDB], m < NDB ? dsf0 : dsf1);
+  };
+
   const float c = p.scale_log2;
 
-  // Unmasked tile, hand-sequenced (see mfma_asm.hpp).  The MFMA pipe is the scarce resource and
-  // the issue port is shared: an MFMA holds it for about 16 of its 32 cycles, which leaves room
-  // for about four ordinary VALU instructions per MFMA (v_exp_f32 counts twice).  A block's
-  // elementwise work is 16 x (fma, exp) + 8 packs for P and 16 x (sub, mul) + 8 packs for dS,
-  // about three slots per MFMA when it is spread over all 32 MFMAs of a block - which needs the
-  // chains of neighbouring blocks to be interleaved, because P can only start after S and dS
-  // only after dP.  Steady state for block b (four chains of 8 MFMAs):
-  //   A  dP(b)   = dO V^T      + P elements 0..6 of block b          LDS: dO^T(b), delta(b)
-  //   B  dK(b-1) += Q^T dS     + P elements 7..14                    LDS: Q rows(b+1)
-  //   C  dV(b)   += dO^T P     + P element 15, dS elements 0..6      LDS: Q^T(b), lse(b+1)
-  //   D  S(b+1)  = Q K^T       + dS elements 7..15                   LDS: dO rows(b+1)
-  // Every operand group is requested at least one chain before the chain that consumes it and
-  // one or two reads per MFMA, never in a burst (a wave issues in order).  The first block of a
-  // tile has no dK in B and the last no S in D; the pipeline is drained at the end of the tile.
+  // Unmasked tile, hand-sequenced (see mfma_asm.hpp).  The dP chain accumulates onto -delta
+  // (stored negated by the delta kernel, it arrives in exactly the C layout of a 32-row block),
+  // so a block's elementwise work is 16 (fma, exp2) + 8 packs for P and 16 multiplies + 8 packs
+  // for dS.  P can only start after S and dS only
+  // after dP, so the chains of neighbouring blocks are interleaved, which spreads that work one
+  // element per MFMA over all 32 MFMAs of a block.  The two chains that accumulate in one
+  // register block (S, dP: each MFMA waits for the previous one) alternate MFMA by MFMA with
+  // the two that rotate over four accumulators (dK, dV).  Steady state for block b:
+  //   X(b): dP(b)_m, dK(b-1)_m, m = 0..7   + P elements 0..14 of block b
+  //         LDS: dO^T(b), Q rows(b+1)
+  //   Y(b): dV(b)_m, S(b+1)_m,  m = 0..7   + P element 15, dS elements 0..15
+  //         LDS: Q^T(b), dO rows(b+1), -lse*log2e(b+1), -delta(b+1)
+  // Every operand group is requested a phase before the phase that consumes it and one or two
+  // reads per MFMA, never in a burst (a wave issues in order).  X(0) has no dK (the previous
+  // block's was issued in the prologue) and the last Y no S.
   auto fast_tile = [&](const StagePtrs& sp_, const TileCopy& next, auto spread_copies) __attribute__((always_inline)) {
     constexpr bool kSpread = decltype(spread_copies)::value;  // copy the next tile piece by piece between the chains
     static_assert(NDB == 4 || NDB == 2, "the schedule below is written for D = 128 (used) and only has to compile for 64");
-    bf16x8 qn[NKS], don[NKS], dotf[2][NDB], qtf[2][NDB];
-    f32x4 l4[4], d4[4];
-    f32x16 s, dp;
+    bf16x8 qn[NKS], don[NKS], dotf[2][NDB];
+    f32x16 s, dp, nl, nd;   // nl: -lse*log2e of the rows of s; nd: -delta of the rows of the next dP chain
     float pr[16], ds[16];
     uint32_t pw[8], dw[8];
-    bf16x8 dsf0, dsf1;
 
     auto tr_frag = [&](int blk, int tile_bytes, int m) __attribute__((always_inline)) {  // fragment m = (sblk, db)
       const int sblk = m / NDB, db = m % NDB;
       const int off = blk + 16 * sblk * ROW_BYTES + tile_bytes;
       return cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
     };
+    auto stat4 = [&](f32x16& dst, int q4, int first_row) __attribute__((always_inline)) {  // rows first_row + 8 q4 + 4h .. +3
+      const f32x4 t = *reinterpret_cast<const f32x4*>(sp_.stat + (first_row + 8 * q4) * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dst[4 * q4 + e] = t[e];
+    };
     auto p_elem = [&](int e, auto lead) __attribute__((always_inline)) {
       if (e >= 2 && (e & 1) == 0) pack_pair(pw[e / 2 - 1], pr[e - 2], pr[e - 1]);  // previous pair, one MFMA after its last exp
-      softmax_elem<decltype(lead)::value>(pr[e], s[e], c, l4[e >> 2][e & 3]);
+      softmax_elem<decltype(lead)::value>(pr[e], s[e], c, nl[e]);
     };
-    auto ds_elem = [&](int e) __attribute__((always_inline)) {
-      dscore_elem(ds[e], pr[e], dp[e], d4[e >> 2][e & 3]);
+    auto ds_elem = [&](int e, auto lead) __attribute__((always_inline)) {
+      mul_elem<decltype(lead)::value>(ds[e], pr[e], dp[e]);
       if (e & 1) pack_pair(dw[e / 2], ds[e - 1], ds[e]);
     };
-    auto spread = [&](int slot_idx) __attribute__((always_inline)) {   // 4 * NB chain slots per tile
+    auto spread = [&](int slot_idx) __attribute__((always_inline)) {   // 4 * NB slots per tile
       if (kSpread) {
         if (slot_idx < kPieces) copy_piece(next, slot_idx);
         if (slot_idx + 4 * NB < kPieces) copy_piece(next, slot_idx + 4 * NB);
       }
     };
 
-    // prologue: operands of block 0 (latency exposed once per tile), then S(0)
+    // prologue: operands of block 0, the pending dK product in the shadow of their latency, S(0)
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], 0);
 #pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) stat4(nl, q4, 0);
+#pragma unroll
     for (int ks = 0; ks < NKS; ++ks) don[ks] = lds_read8(sp_.nat[ks], TILE_BYTES);
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) l4[q4] = *reinterpret_cast<const f32x4*>(sp_.stat + (8 * q4) * 4);
+    for (int q4 = 0; q4 < 4; ++q4) stat4(nd, q4, BQ);
+    asm_fence();
+    if (pending) flush_pending();
     asm_fence();
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
@@ -437,73 +464,78 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     for (int rb = 0; rb < NB; ++rb) {
       const int blk = 32 * rb * ROW_BYTES;
       const bool more = rb + 1 < NB;
-      // ---- A: dP(b) with P elements 0..6; reads dO^T(b) and delta(b)
-      spread(4 * rb + 0);
+      // ---- X(b)
 #pragma unroll
       for (int m = 0; m < NKS; ++m) {
-        if (m == 0) mfma_first_b_agpr(dp, don[0], vf[0]);
+        if (m == 0) spread(4 * rb + 0);
+        if (m == NKS / 2) spread(4 * rb + 1);
+        if (m == 0) mfma_first_cin_b_agpr(dp, don[0], vf[0], nd);
         else mfma_next_b_agpr(dp, don[m], vf[m]);
         if (m < 2 * NDB) dotf[m / NDB][m % NDB] = tr_frag(blk, TILE_BYTES, m);
-        if ((m & 1) == 0) d4[m / 2] = *reinterpret_cast<const f32x4*>(sp_.stat + (BQ + 32 * rb + 8 * (m / 2)) * 4);
-        if (m == 1) p_elem(0, std::true_type{});
-        if (m > 1) p_elem(m - 1, std::false_type{});
-        asm_fence();
+        if (rb == 0) {
+          // no dK chain to alternate with: two elements per MFMA (element 14 follows in Y)
+          if (m == 1) { p_elem(0, std::true_type{}); p_elem(1, std::false_type{}); }
+          if (m > 1) { p_elem(2 * m - 2, std::false_type{}); p_elem(2 * m - 1, std::false_type{}); }
+          if (more) qn[m] = lds_read8(sp_.nat[m], blk + 32 * ROW_BYTES);
+          asm_fence();
+        } else {
+          if (m > 0) p_elem(2 * m - 1, std::false_type{});
+          asm_fence();
+          mfma_acc_agpr(dkacc[m % NDB], qtf[m / NDB][m % NDB], m < NDB ? dsf0 : dsf1);
+          if (more) qn[m] = lds_read8(sp_.nat[m], blk + 32 * ROW_BYTES);
+          if (m == 0) p_elem(0, std::true_type{});
+          else p_elem(2 * m, std::false_type{});
+          asm_fence();
+        }
       }
-      // ---- B: dK(b-1) with P elements 7..14; reads the Q rows of block b+1
-      spread(4 * rb + 1);
+      // ---- Y(b)
+      bf16x8 pf0, pf1;
 #pragma unroll
       for (int m = 0; m < 2 * NDB; ++m) {
-        if (rb > 0) mfma_acc_agpr(dkacc[m % NDB], qtf[m / NDB][m % NDB], m < NDB ? dsf0 : dsf1);
-        if (more && m < NKS) qn[m] = lds_read8(sp_.nat[m], blk + 32 * ROW_BYTES);
-        p_elem(7 + m, std::false_type{});
-        asm_fence();
-      }
-      // ---- C: dV(b) with P element 15 and dS elements 0..6; reads Q^T(b) and lse(b+1)
-      spread(4 * rb + 2);
-      const bf16x8 pf0 = frag_from_words(pw[0], pw[1], pw[2], pw[3]);
-#pragma unroll
-      for (int m = 0; m < NDB; ++m) {
-        mfma_acc_agpr(dvacc[m], dotf[0][m], pf0);
-        qtf[0][m] = tr_frag(blk, 0, m);
-        if (m == 0) softmax_elem<false>(pr[15], s[15], c, l4[3][3]);
-        if (m == 1) pack_pair(pw[7], pr[14], pr[15]);
-        if (m >= 1) ds_elem(m - 1);
-        asm_fence();
-      }
-      const bf16x8 pf1 = frag_from_words(pw[4], pw[5], pw[6], pw[7]);
-#pragma unroll
-      for (int m = 0; m < NDB; ++m) {
-        mfma_acc_agpr(dvacc[m], dotf[1][m], pf1);
-        qtf[1][m] = tr_frag(blk, 0, NDB + m);
-        if (more) l4[m] = *reinterpret_cast<const f32x4*>(sp_.stat + (32 * (rb + 1) + 8 * m) * 4);
-        ds_elem(NDB - 1 + m);
-        asm_fence();
-      }
-      // ---- D: S(b+1) with dS elements 7..15; reads the dO rows of block b+1
-      spread(4 * rb + 3);
-#pragma unroll
-      for (int m = 0; m < NKS; ++m) {
+        if (m == 0) spread(4 * rb + 2);
+        if (m == NDB) spread(4 * rb + 3);
+        if (m == 0) pf0 = frag_from_words(pw[0], pw[1], pw[2], pw[3]);
+        if (m == NDB) pf1 = frag_from_words(pw[4], pw[5], pw[6], pw[7]);
+        mfma_acc_agpr(dvacc[m % NDB], dotf[m / NDB][m % NDB], m < NDB ? pf0 : pf1);
+        qtf[m / NDB][m % NDB] = tr_frag(blk, 0, m);
         if (more) {
+          if (m == 0 && rb == 0) p_elem(14, std::false_type{});
+          if (m == 0) softmax_elem<false>(pr[15], s[15], c, nl[15]);
+          if (m > 0) ds_elem(2 * m - 1, std::false_type{});
+          asm_fence();
           if (m == 0) mfma_first_b_agpr(s, qn[0], kf[0]);
           else mfma_next_b_agpr(s, qn[m], kf[m]);
           don[m] = lds_read8(sp_.nat[m], blk + 32 * ROW_BYTES + TILE_BYTES);
+          if (m >= 1 && m <= 4) stat4(nl, m - 1, 32 * (rb + 1));   // element 15 has read nl[15] in slot 0
+          if (m >= NKS - 4) stat4(nd, m - (NKS - 4), BQ + 32 * (rb + 1));
+          if (m == 0) { pack_pair(pw[7], pr[14], pr[15]); ds_elem(0, std::true_type{}); }
+          else ds_elem(2 * m, std::false_type{});
+          if (m == NKS - 1) ds_elem(15, std::false_type{});
+          asm_fence();
+        } else {
+          // last block of the tile, no S chain to alternate with: two elements per MFMA
+          if (m == 0) softmax_elem<false>(pr[15], s[15], c, nl[15]);
+          if (m == 1) { pack_pair(pw[7], pr[14], pr[15]); ds_elem(0, std::true_type{}); ds_elem(1, std::false_type{}); }
+          if (m > 1) { ds_elem(2 * m - 2, std::false_type{}); ds_elem(2 * m - 1, std::false_type{}); }
+          if (m == NKS - 1) { ds_elem(14, std::false_type{}); ds_elem(15, std::false_type{}); }
+          asm_fence();
         }
-        ds_elem(2 * NDB - 1 + m);
-        if (m == NKS - 1) ds_elem(2 * NDB - 1 + NKS);
-        asm_fence();
       }
       dsf0 = frag_from_words(dw[0], dw[1], dw[2], dw[3]);
       dsf1 = frag_from_words(dw[4], dw[5], dw[6], dw[7]);
     }
-    // drain: dK of the last block
-#pragma unroll
-    for (int m = 0; m < 2 * NDB; ++m) mfma_acc_agpr(dkacc[m % NDB], qtf[m / NDB][m % NDB], m < NDB ? dsf0 : dsf1);
+    pending = true;
   };
 
   // Generic tile (diagonal, document end, D = 64): compiler-scheduled, with masks.
   // kPin keeps LDS reads from crossing the phase boundaries but lets ALU and MFMA instructions move.
   constexpr int kPin = 0x1 | 0x2 | 0x4 | 0x8 | 0x400;
   auto generic_tile = [&](const StagePtrs& sp_, const int i0) __attribute__((always_inline)) {
+    if (pending) {
+      flush_pending();
+      mfma_result_fence();  // the compiler's own instructions may touch dkacc next
+      pending = false;
+    }
     bf16x8 qn[NKS];
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], 0);
@@ -525,15 +557,15 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
         }
       __builtin_amdgcn_sched_barrier(kPin);
       f32x16 dp = mfma_chain_b_in_agpr<NKS>(don, vf);
-      bf16x8 qtf[2][NDB];
+      bf16x8 qtg[2][NDB];
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const int off = blk + 16 * sblk * ROW_BYTES;
-          qtf[sblk][db] = cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
+          qtg[sblk][db] = cat4(lds_read_tr4(sp_.tr0[db] + off), lds_read_tr4(sp_.tr8[db] + off));
         }
-      // row statistics of the block's 16 rows held by this lane
+      // row statistics (-lse*log2e, -delta) of the block's 16 rows held by this lane
       f32x4 l4[4], d4[4];
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
@@ -558,8 +590,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int r = 8 * sblk + 2 * t;
-          pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[r >> 2][r & 3]));
-          pr[r + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], c, -l4[r >> 2][(r & 3) + 1]));
+          pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, l4[r >> 2][r & 3]));
+          pr[r + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], c, l4[r >> 2][(r & 3) + 1]));
           pp[t] = pack_bf16(pr[r], pr[r + 1]);
         }
         pf[sblk] = cat_pairs(pp[0], pp[1], pp[2], pp[3]);
@@ -575,7 +607,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int r = 8 * sblk + 2 * t;
-          dd[t] = pack_bf16(pr[r] * (dp[r] - d4[r >> 2][r & 3]), pr[r + 1] * (dp[r + 1] - d4[r >> 2][(r & 3) + 1]));
+          dd[t] = pack_bf16(pr[r] * (dp[r] + d4[r >> 2][r & 3]), pr[r + 1] * (dp[r + 1] + d4[r >> 2][(r & 3) + 1]));
         }
         dsf[sblk] = cat_pairs(dd[0], dd[1], dd[2], dd[3]);
       }
@@ -587,7 +619,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) dkacc[db] = mfma32(qtf[sblk][db], dsf[sblk], dkacc[db]);
+        for (int db = 0; db < NDB; ++db) dkacc[db] = mfma32(qtg[sblk][db], dsf[sblk], dkacc[db]);
     }
   };
 
@@ -640,6 +672,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     step_fn(st + 1, std::integral_constant<int, 1>{});
   }
   if (st < total) step_fn(st, std::integral_constant<int, 0>{});
+  if (pending) flush_pending();
   mfma_result_fence();  // the last assembly MFMAs have retired before the accumulators are read
 #ifdef IE_EXP_TIMING
   if (tid == 0) {

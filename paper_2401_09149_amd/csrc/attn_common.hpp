@@ -99,7 +99,17 @@ __device__ __forceinline__ bf16x8 global_load_to_agpr(const void* ptr) {
   asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(r) : "v"(ptr) : "memory");
   return r;
 }
-__device__ __forceinline__ void agpr_loads_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// A fragment computed in VGPRs, moved into accumulation registers through a lane-private
+// 16-byte LDS slot (`lds_addr`, 16-byte aligned): there is no 128-bit VGPR->AGPR move, and a
+// value the compiler itself holds is copied over again before every assembly use.  A wave's
+// LDS operations complete in order, so the read returns what the write stored.  As above,
+// call agpr_loads_wait() before the first use.
+__device__ __forceinline__ bf16x8 move_to_agpr_via_lds(bf16x8 x, uint32_t lds_addr) {
+  bf16x8 r;
+  asm volatile("ds_write_b128 %1, %2\n\tds_read_b128 %0, %1" : "=a"(r) : "v"(lds_addr), "v"(x) : "memory");
+  return r;
+}
+__device__ __forceinline__ void agpr_loads_wait() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); }
 
 // Exchange between the two half-waves with v_permlane32_swap: given (a, b) it returns
 // r0 = {a[0..31], b[0..31]} and r1 = {a[32..63], b[32..63]}.  With a == b == x, lane l
@@ -293,6 +303,14 @@ struct AsyncTile {
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// x * f, element by element, rounded back to bf16 (nearest even).
+__device__ __forceinline__ bf16x8 scale_frag(bf16x8 x, float f) {
+  bf16x8 r;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) r[t] = (__bf16)((float)x[t] * f);
+  return r;
+}
 
 // Rounds two floats to bf16 (nearest even) into one register.
 __device__ __forceinline__ bf16x2 pack_bf16(float a, float b) {

@@ -93,6 +93,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
 
   const int wave_row_min = (int)(q0 - k_begin) + wv * 32;
+#ifdef IE_EXP_TIMING
+  const unsigned long long t_begin = __builtin_readcyclecounter(), w_begin = wall_clock64();
+#endif
 
   // One 64-key LDS tile is consumed as two 32-key blocks, each with its own softmax update.
   // `stage` is the byte offset of the stage holding tile kt; FULL_NEXT says that tile kt+1
@@ -121,6 +124,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
       f32x16 s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#ifdef IE_EXP_PRIO
+      __builtin_amdgcn_s_setprio(IE_EXP_PRIO);
+#endif
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
 #ifdef IE_EXP_NO_LDS
@@ -130,6 +136,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
 #endif
       }
 
+#ifdef IE_EXP_PRIO
+      __builtin_amdgcn_s_setprio(0);
+#endif
       // V^T fragments of this block: requested now, consumed after the exponentials
       bf16x8 vfrag[2][NDB];
 #pragma unroll
@@ -186,10 +195,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
         pf[sblk] = cat_pairs(pr[0], pr[1], pr[2], pr[3]);
       }
       // O^T += V^T P^T
+#ifdef IE_EXP_PRIO
+      __builtin_amdgcn_s_setprio(IE_EXP_PRIO);
+#endif
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) oacc[db] = mfma32(vfrag[sblk][db], pf[sblk], oacc[db]);
+#ifdef IE_EXP_PRIO
+      __builtin_amdgcn_s_setprio(0);
+#endif
     }
     async_wait_all();  // the copies of the next stage have landed ...
     __syncthreads();   // ... for every wave, and every wave is done reading this stage
@@ -221,8 +236,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
         for (int t = 0; t < 4; ++t) w[t] = (__bf16)(oacc[db][4 * q4 + t] * inv_l);
         *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * q4 + 4 * h) = w;
       }
+#ifndef IE_EXP_TIMING
     if (h == 0) p.lse_out[((int64_t)tc.b * p.Hq + tc.h) * p.S + row] = (m * c + __builtin_amdgcn_logf(l_full)) * kLn2;
+#endif
   }
+#ifdef IE_EXP_TIMING
+  if (tid == 0) {  // timing build: the lse buffer carries (shader cycles, 100 MHz ticks, key tiles) per workgroup instead
+    unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.lse_out) + (size_t)blockIdx.x * 4;
+    dbg[0] = __builtin_readcyclecounter() - t_begin;
+    dbg[1] = wall_clock64() - w_begin;
+    dbg[2] = nkt;
+  }
+#endif
 }
 
 template <int D>

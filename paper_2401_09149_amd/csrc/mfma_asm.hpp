@@ -22,6 +22,10 @@ namespace ie {
 __device__ __forceinline__ void mfma_first_b_agpr(f32x16& acc, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
 }
+// acc(VGPR) = cin(VGPR) + A(VGPR) * B(AGPR); acc and cin are distinct registers
+__device__ __forceinline__ void mfma_first_cin_b_agpr(f32x16& acc, const bf16x8& a, const bf16x8& b, const f32x16& cin) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "a"(b), "v"(cin));
+}
 // acc(VGPR) += A(VGPR) * B(AGPR)
 __device__ __forceinline__ void mfma_next_b_agpr(f32x16& acc, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
@@ -65,15 +69,17 @@ __device__ __forceinline__ void dscore_pair(uint32_t& packed, float p0, float p1
 }
 
 // Single-element forms, for schedules that give every MFMA at most ~4 VALU slots.
-// p = exp2(s*c - l).  LEAD: the first use of an MFMA chain's result (see file header).
+// p = exp2(s*c + nl), nl = -lse*log2(e).  LEAD: the first use of an MFMA chain's result (see file header).
 template <bool LEAD>
-__device__ __forceinline__ void softmax_elem(float& p, float s, float c, float l) {
+__device__ __forceinline__ void softmax_elem(float& p, float s, float c, float nl) {
   if (LEAD) asm volatile("s_nop 9");
-  asm volatile("v_fma_f32 %0, %1, %2, -%3\n\tv_exp_f32 %0, %0" : "=&v"(p) : "v"(s), "s"(c), "v"(l));
+  asm volatile("v_fma_f32 %0, %1, %2, %3\n\tv_exp_f32 %0, %0" : "=&v"(p) : "v"(s), "s"(c), "v"(nl));
 }
-// d = p * (dp - delta)
-__device__ __forceinline__ void dscore_elem(float& d, float p, float dp, float delta) {
-  asm volatile("v_sub_f32 %0, %2, %3\n\tv_mul_f32 %0, %0, %1" : "=&v"(d) : "v"(p), "v"(dp), "v"(delta));
+// d = p * dp  (the dP chain started from -delta)
+template <bool LEAD>
+__device__ __forceinline__ void mul_elem(float& d, float p, float dp) {
+  if (LEAD) asm volatile("s_nop 9");
+  asm volatile("v_mul_f32 %0, %1, %2" : "=v"(d) : "v"(p), "v"(dp));
 }
 // packed = {bf16(a), bf16(b)}.  When a or b comes from v_exp_f32, at least one other instruction
 // must have been issued since (the callers put an MFMA in between).

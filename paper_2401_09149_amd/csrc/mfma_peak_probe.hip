@@ -5,7 +5,10 @@
 // (little switching activity), and N(0,1)-like values cycling through 8 register sets so that
 // consecutive MFMAs see different inputs, as in a real contraction.
 //
-// Prints TFLOP/s and the clock that figure implies at 1024 FLOP/clk/SIMD x 4 SIMD x 256 CU.
+// Prints TFLOP/s and the clock that figure implies at 1024 FLOP/clk/SIMD x 4 SIMD x 256 CU,
+// and - from the shader cycle counter and the constant 100 MHz counter read inside the kernel -
+// how many shader cycles one MFMA took (32 = the pipe never idles) and the shader clock the
+// kernel actually ran at: the two ways a power limit can show.
 #include <hip/hip_runtime.h>
 
 #include <chrono>
@@ -34,8 +37,9 @@ __device__ float pseudo_normal(unsigned& h) {  // sum of three uniforms, unit-is
 }
 
 template <int NSET, bool RANDOM>
-__global__ __launch_bounds__(256) void mfma_loop(float* out, int iters) {
+__global__ __launch_bounds__(256) void mfma_loop(float* out, unsigned long long* ticks, int iters) {
   const int tid = threadIdx.x;
+  const unsigned long long c0 = __builtin_readcyclecounter(), w0 = wall_clock64();
   unsigned h = tid * 2654435761u + blockIdx.x * 40503u + 12345u;
   bf16x8 a[NSET], b[NSET];
   for (int i = 0; i < NSET; ++i)
@@ -55,10 +59,14 @@ __global__ __launch_bounds__(256) void mfma_loop(float* out, int iters) {
   for (int i = 0; i < 4; ++i)
     for (int r = 0; r < 16; ++r) s += c[i][r];
   out[blockIdx.x * 256 + tid] = s;
+  if (tid == 0) {
+    ticks[2 * blockIdx.x] = __builtin_readcyclecounter() - c0;
+    ticks[2 * blockIdx.x + 1] = wall_clock64() - w0;
+  }
 }
 
 template <int NSET, bool RANDOM>
-void run(float* out, int cus, const char* name, double seconds) {
+void run(float* out, unsigned long long* ticks, int cus, const char* name, double seconds) {
   const int iters = 20000;  // 16 MFMAs of 32768 FLOP per trip and wave
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0));
@@ -68,7 +76,7 @@ void run(float* out, int cus, const char* name, double seconds) {
   double elapsed = 0.0;
   while (elapsed < seconds) {
     CK(hipEventRecord(e0));
-    mfma_loop<NSET, RANDOM><<<cus, 256>>>(out, iters);
+    mfma_loop<NSET, RANDOM><<<cus, 256>>>(out, ticks, iters);
     CK(hipEventRecord(e1));
     CK(hipEventSynchronize(e1));
     CK(hipEventElapsedTime(&ms, e0, e1));
@@ -78,6 +86,13 @@ void run(float* out, int cus, const char* name, double seconds) {
   const double tflops = flop / (ms * 1e-3) / 1e12;
   const double ghz = tflops * 1e12 / ((double)cus * 4 * 1024.0) / 1e9;
   std::printf("%-52s %8.1f TFLOP/s after %.1f s  (= %.2f GHz at 1024 FLOP/clk/SIMD)\n", name, tflops, elapsed, ghz);
+  unsigned long long* h = (unsigned long long*)std::malloc((size_t)cus * 16);
+  CK(hipMemcpy(h, ticks, (size_t)cus * 16, hipMemcpyDeviceToHost));
+  double cyc = 0, wall = 0;
+  for (int i = 0; i < cus; ++i) { cyc += (double)h[2 * i]; wall += (double)h[2 * i + 1]; }
+  std::free(h);
+  std::printf("%-52s %8.2f shader cycles per MFMA, shader clock %.3f GHz (last launch, mean over workgroups)\n", "",
+              cyc / cus / ((double)iters * 16), cyc / wall * 0.1);
 }
 
 int main(int argc, char** argv) {
@@ -87,8 +102,11 @@ int main(int argc, char** argv) {
   std::printf("device: %s, %d CUs, clock rate %.2f GHz\n", prop.gcnArchName, prop.multiProcessorCount, prop.clockRate / 1e6);
   float* out;
   CK(hipMalloc(&out, (size_t)prop.multiProcessorCount * 256 * sizeof(float)));
-  run<1, false>(out, prop.multiProcessorCount, "32x32x16 bf16, constant small-integer operands", seconds);
-  run<8, true>(out, prop.multiProcessorCount, "32x32x16 bf16, N(0,1) operands, 8 sets cycled", seconds);
+  unsigned long long* ticks;
+  CK(hipMalloc(&ticks, (size_t)prop.multiProcessorCount * 16));
+  run<1, false>(out, ticks, prop.multiProcessorCount, "32x32x16 bf16, constant small-integer operands", seconds);
+  run<8, true>(out, ticks, prop.multiProcessorCount, "32x32x16 bf16, N(0,1) operands, 8 sets cycled", seconds);
+  CK(hipFree(ticks));
   CK(hipFree(out));
   return 0;
 }

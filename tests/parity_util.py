@@ -32,9 +32,17 @@ def run_gpu(q, k, v, dout, scale, causal, cu):
     return o, lse, dq, dk, dv
 
 
+# Below this RMS magnitude a reference gradient counts as zero: with a single visible key
+# dS = P (dP - delta) vanishes identically, the fp64 reference is rounding noise, and the fp32
+# path leaves the difference of two sums of D products of O(1) terms (about 1e-7 each); a
+# relative error against that is meaningless.  The absolute bar applies regardless.
+REL_FLOOR_RMS = 1e-4
+
+
 def grad_errors(got, ref):
     d = got - ref
-    return float(np.abs(d).max()), float(np.linalg.norm(d) / max(np.linalg.norm(ref), 1e-300))
+    floor = REL_FLOOR_RMS * np.sqrt(ref.size)
+    return float(np.abs(d).max()), float(np.linalg.norm(d) / max(np.linalg.norm(ref), floor))
 
 
 def compare_all(got, ref, label="", grad_abs_tol=TOL_GRAD_ABS):
