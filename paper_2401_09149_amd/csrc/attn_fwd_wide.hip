@@ -1,0 +1,461 @@
+// Forward kernel for head dimension 128, one wave per SIMD: O = softmax(scale * Q K^T + mask) V
+// and the per-row log-sum-exp (fused attention of Sec. 2.1 / Sec. 4.2, recast for CDNA4).
+//
+// One workgroup per (batch, head, 256-query tile); each of the 4 wavefronts owns 64 query rows
+// as two 32-row column blocks "a" and "b", whose Q fragments and O^T accumulators stay in
+// AGPRs for the whole kernel.  128-key K and V tiles stream through two LDS stages filled by
+// asynchronous copies.  Scores are produced transposed, S^T = K Q^T (one query column per
+// lane, see attn_fwd.hip), and every K and V^T fragment read from LDS feeds two MFMAs, one per
+// column block.
+//
+// Unmasked tiles run a hand-sequenced pipeline (mfma_asm.hpp).  The softmax of a 32x32 block is
+// about 70 VALU instructions against 16 MFMAs, more than fits in the MFMAs' shadow if the two
+// are not interleaved instruction by instruction, so the two column blocks are staggered by
+// half a block and each phase pairs the MFMAs of one with the softmax of the other
+// (i = 32-key block index):
+//   A_i: S_a(i+1)_k, PV_a(i)_k alternating, k = 0..7  + softmax of s_b(i)    reads V^T(i+1)
+//   B_i: S_b(i+1)_k, PV_b(i)_k alternating            + softmax of s_a(i+1)  reads K(i+2)
+// K(i) is read during B_(i-2) and V^T(i) during A_(i-1), so the four blocks of tile T are read
+// during the eight phases B_(4T-2) .. A_(4T+2): that is one "round", and the workgroup barrier
+// that publishes the next stage and releases this one sits between A_(4T+2) and B_(4T+2).  The
+// pipeline never drains at a tile boundary; it is filled in a wave's first round and drained
+// after its last unmasked tile.  Tiles that need a mask for this wave (the diagonal, the end of
+// a document) take a compiler-scheduled path afterwards.
+#include <type_traits>
+
+#include "attn_common.hpp"
+#include "launch.hpp"
+#include "mfma_asm.hpp"
+
+namespace ie {
+
+struct FwdWideCfg {
+  static constexpr int D = 128;
+  static constexpr int BM = 256;                       // query rows per workgroup
+  static constexpr int BN = 128;                       // keys per stage
+  static constexpr int NB = BN / 32;                   // 32-key blocks per stage
+  static constexpr int ROW_BYTES = D * 2;
+  static constexpr int PART_BYTES = 64 * ROW_BYTES;    // the asynchronous copy works on 64-row parts
+  static constexpr int TILE_BYTES = BN * ROW_BYTES;    // one K or V tile
+  static constexpr int V_BASE = 2 * TILE_BYTES;        // LDS: K stage 0 | K stage 1 | V stage 0 | V stage 1
+  static constexpr int SMEM_BYTES = 4 * TILE_BYTES;
+};
+
+// Softmax state of one 32-query column block (one query per lane, both half-waves alike).
+struct ColState {
+  float m;      // reference maximum, raw score units (lazy: moves only when exceeded by kSlack)
+  float negmc;  // -m * scale * log2(e)
+  float thr;    // m + slack
+  float l;      // this lane's share of the row sum
+};
+
+__global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p) {
+  using C = FwdWideCfg;
+  constexpr int D = C::D, BM = C::BM, BN = C::BN, NB = C::NB;
+  constexpr int NKS = D / 16, NDB = D / 32;
+  constexpr int ROW_BYTES = C::ROW_BYTES, TILE_BYTES = C::TILE_BYTES, V_BASE = C::V_BASE;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ int scratch[8];
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
+
+  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch);
+  if (!tc.valid) return;
+  const int g = tc.h / (p.Hq / p.Hkv);
+  const int64_t q0 = tc.t0;
+  const int64_t q_end = (q0 + BM < tc.doc_end) ? q0 + BM : tc.doc_end;
+  const int64_t k_begin = tc.doc_begin;
+  const int64_t k_end = p.causal ? q_end : tc.doc_end;
+  // (the tile coordinates may have come through LDS: tell the compiler they are wave-uniform)
+  const int nk = (int)uniform((uint32_t)(k_end - k_begin));  // visible keys of the tile (before the per-row causal cut)
+  const int nkt = (nk + BN - 1) / BN;
+
+  const int64_t q_stride = (int64_t)p.Hq * D;
+  const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
+  const __bf16* qbase = p.q + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D;
+  const char* kbase = uniform(reinterpret_cast<const char*>(p.k + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D));
+  const char* vbase = uniform(reinterpret_cast<const char*>(p.v + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D));
+  const int64_t tile_pitch = BN * kv_pitch;
+
+  const uint32_t lds0 = lds_address(smem);
+  AsyncTile<D> ld;
+  ld.init(tid, kv_pitch);
+  const int wave_u = ld.wave;
+
+  // Asynchronous copy of key tile T into stage T & 1: all at once (any number of valid rows), or
+  // piece by piece for a complete tile (16 pieces per wave: 2 tensors x 2 parts x 4 instructions).
+  static_assert(2 * (BN / 64) * AsyncTile<D>::NI == 16, "two pieces per phase, eight phases per round");
+  auto copy_all = [&](const int T) __attribute__((always_inline)) {
+    const int rows = nk - T * BN;  // >= 1
+    const uint32_t base = lds0 + (T & 1) * TILE_BYTES;
+#pragma unroll
+    for (int part = 0; part < BN / 64; ++part) {
+      const int first = rows > 64 * part ? 64 * part : rows - 1;  // a part past the end repeats the last row
+      const int valid = rows > 64 * part ? rows - 64 * part : 1;
+      ld.load(base + part * C::PART_BYTES, kbase + T * tile_pitch + (int64_t)first * kv_pitch, valid);
+      ld.load(base + V_BASE + part * C::PART_BYTES, vbase + T * tile_pitch + (int64_t)first * kv_pitch, valid);
+    }
+  };
+  auto copy_piece = [&](const int T, const int k) __attribute__((always_inline)) {
+    constexpr int NI = AsyncTile<D>::NI, RPI = AsyncTile<D>::RPI;
+    const int tensor = k / ((BN / 64) * NI), part = (k / NI) % (BN / 64), i = k % NI;
+    const int row = 64 * part + 4 * RPI * i;
+    async_copy16(ld.voff, (tensor ? vbase : kbase) + T * tile_pitch + (int64_t)row * kv_pitch,
+                 lds0 + (T & 1) * TILE_BYTES + tensor * V_BASE + part * C::PART_BYTES + (i * 4 + wave_u) * 1024);
+  };
+  copy_all(0);
+
+  // This lane's two query rows (clamped into the tile: out-of-range lanes repeat the last row).
+  int64_t row_a = q0 + wv * 64 + n, row_b = row_a + 32;
+  const bool ok_a = row_a < q_end, ok_b = row_b < q_end;
+  if (!ok_a) row_a = q_end - 1;
+  if (!ok_b) row_b = q_end - 1;
+  const int rel_a = (int)(row_a - k_begin), rel_b = (int)(row_b - k_begin);
+
+  bf16x8 qa[NKS], qb[NKS];  // live in AGPRs: B operand of S^T = K Q^T, column n = query
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) {
+    qa[ks] = global_load_to_agpr(qbase + row_a * q_stride + ks * 16 + h * 8);
+    qb[ks] = global_load_to_agpr(qbase + row_b * q_stride + ks * 16 + h * 8);
+  }
+
+  // Per-lane LDS addresses in stage 0; stage, block and half-block offsets are immediates.
+  const char* kp[NKS];   // K tile, A operand: row = key n of a block, chunk = 2ks + h
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) kp[ks] = smem + tile_off<D>(n, 2 * ks + h);
+  const char* vp0[NDB];  // V tile, transpose loads: rows 4h.. and 8+4h.. of each 16-key group
+  const char* vp8[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    vp0[db] = smem + V_BASE + tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    vp8[db] = smem + V_BASE + tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+  }
+
+  const float c = p.scale_log2;
+  constexpr float kSlack = 8.0f;  // log2 units, see attn_fwd.hip
+  const float slack_raw = kSlack / c;
+  ColState sa{-INFINITY, INFINITY, -INFINITY, 0.f}, sb{-INFINITY, INFINITY, -INFINITY, 0.f};
+  f32x16 oa[NDB], ob[NDB];  // live in AGPRs
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { oa[db][r] = 0.f; ob[db][r] = 0.f; }
+
+  // The reference maximum of a column block moves: rescale its accumulators.  Rare after the
+  // first blocks of a row.  The accumulators are AGPRs that assembly MFMAs write: fenced.
+  auto rescale = [&](ColState& st, f32x16 (&o)[NDB], const float mx) __attribute__((always_inline)) {
+    mfma_result_fence();
+    const float m_new = fmaxf(st.m, mx);
+    const float alpha = __builtin_amdgcn_exp2f((st.m - m_new) * c);
+    st.m = m_new;
+    st.negmc = -m_new * c;
+    st.thr = m_new + slack_raw;
+    st.l *= alpha;
+    // element by element through one VGPR, in assembly: left to the compiler, the multiplications
+    // pull the accumulators out of the AGPRs for whole phases
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float tmp;
+        asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                     : "+a"(o[db][r]), "=&v"(tmp)
+                     : "v"(alpha));
+      }
+    mfma_result_fence();
+  };
+
+  // ---- pipeline state that crosses phase and round boundaries
+  const int wave_row_min = (int)uniform((uint32_t)((int)(q0 - k_begin) + wv * 64));
+  bf16x8 kf[NKS];          // K fragments of the block whose scores come next
+  bf16x8 vt[2][2][NDB];    // V^T fragments, double-buffered by block parity: [parity][16-key half][db]
+  f32x16 s_a, s_b;         // scores of the current block of each column block
+  uint32_t pw_a[8], pw_b[8];  // packed probabilities (bf16 pairs) of each column block
+  float pr_a[16], pr_b[16];   // exponentials waiting to be summed and packed
+  float t_a, t_b;             // running column maxima
+
+  // Element e of a softmax: its exponential; the sum takes the previous element and the pack the
+  // previous pair, so that neither reads a v_exp_f32 result in the very next instruction.
+  auto elem = [&](float (&pr)[16], uint32_t (&pw)[8], const f32x16& s, ColState& st, const int e) __attribute__((always_inline)) {
+    exp_elem(pr[e], s[e], c, st.negmc);
+    if (e >= 1) add_to(st.l, pr[e - 1]);
+    if (e >= 2 && (e & 1) == 0) pack_pair(pw[e / 2 - 1], pr[e - 2], pr[e - 1]);
+  };
+
+  // One phase: 16 MFMA slots.  X is the column block whose MFMAs run (S of block i+1 on even
+  // slots, PV of block i on odd slots), Y the one whose softmax runs (on s_y).  KLOAD / VLOAD: after a
+  // K fragment's last use load the next block's (r = local block index in stage STG, or -1);
+  // load the next block's V^T into the other buffer.
+  // TAIL: X's previous softmax left its last sum and pack for slot 0.
+  auto phase = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, const bf16x8 (&qx)[NKS], f32x16& s_x,
+                   f32x16 (&o_x)[NDB], uint32_t (&pw_x)[8], float (&pr_x)[16], ColState& st_x, f32x16& s_y,
+                   f32x16 (&o_y)[NDB], uint32_t (&pw_y)[8], float (&pr_y)[16], float& t_y, ColState& st_y, auto vpar_c,
+                   auto kload_c, auto vload_c, const int copy_tile, auto slot_c)
+      __attribute__((always_inline)) {
+    constexpr bool HAS_S = decltype(has_s)::value, HAS_PV = decltype(has_pv)::value;
+    constexpr bool HAS_SM = decltype(has_sm)::value, HAS_TAIL = decltype(has_tail)::value;
+    constexpr int vpar = decltype(vpar_c)::value, kload_off = decltype(kload_c)::value;
+    constexpr int vload_off = decltype(vload_c)::value, copy_slot = decltype(slot_c)::value;
+    bf16x8 pf0, pf1;
+#pragma unroll
+    for (int pos = 0; pos < 16; ++pos) {
+      const int k = pos >> 1;
+      if (copy_tile >= 0 && (pos == 0 || pos == 8)) copy_piece(copy_tile, 2 * copy_slot + (pos >> 3));
+      // ---- the MFMA of this slot, and the LDS read that can follow it
+      if ((pos & 1) == 0) {
+        if (HAS_S) {
+          if (k == 0) mfma_first_b_agpr(s_x, kf[0], qx[0]);
+          else mfma_next_b_agpr(s_x, kf[k], qx[k]);
+        }
+        if (kload_off >= 0) kf[k] = lds_read8(kp[k], kload_off);
+      } else {
+        if (HAS_PV) {
+          if (k == 0) pf0 = frag_from_words(pw_x[0], pw_x[1], pw_x[2], pw_x[3]);
+          if (k == NDB) pf1 = frag_from_words(pw_x[4], pw_x[5], pw_x[6], pw_x[7]);
+          mfma_acc_agpr(o_x[k % NDB], vt[vpar][k / NDB][k % NDB], k < NDB ? pf0 : pf1);
+        }
+        if (vload_off >= 0) {
+          const int off = vload_off + 16 * (k / NDB) * ROW_BYTES;
+          vt[vpar ^ 1][k / NDB][k % NDB] = cat4(lds_read_tr4(vp0[k % NDB] + off), lds_read_tr4(vp8[k % NDB] + off));
+        }
+      }
+      // ---- the VALU work of this slot
+      if (HAS_TAIL && pos == 0) {
+        add_to(st_x.l, pr_x[15]);
+        pack_pair(pw_x[7], pr_x[14], pr_x[15]);
+      }
+      if (HAS_SM) {
+        if (pos == 1) colmax_lo<true>(t_y, s_y);
+        if (pos == 2) colmax_hi(t_y, s_y);
+        if (pos == 3) {
+          halfwave_max_asm(t_y);
+          if (__builtin_amdgcn_ballot_w64(t_y > st_y.thr) != 0) rescale(st_y, o_y, t_y);
+        }
+        // slots 4..7 take two elements each (0..7), slots 8..15 one each (8..15)
+        if (pos >= 4 && pos < 8) { elem(pr_y, pw_y, s_y, st_y, 2 * (pos - 4)); elem(pr_y, pw_y, s_y, st_y, 2 * (pos - 4) + 1); }
+        if (pos >= 8) elem(pr_y, pw_y, s_y, st_y, pos);
+      }
+      asm_fence();
+    }
+  };
+  // shorthands for the two kinds of phase
+  using Y = std::true_type;
+  using N = std::false_type;
+  using None = std::integral_constant<int, -1>;
+  auto phase_a = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, auto vpar, auto vload_off, int copy_tile, auto copy_slot)
+      __attribute__((always_inline)) {
+    phase(has_s, has_pv, has_sm, has_tail, qa, s_a, oa, pw_a, pr_a, sa, s_b, ob, pw_b, pr_b, t_b, sb, vpar, None{}, vload_off, copy_tile, copy_slot);
+  };
+  auto phase_b = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, auto vpar, auto kload_off, int copy_tile, auto copy_slot)
+      __attribute__((always_inline)) {
+    phase(has_s, has_pv, has_sm, has_tail, qb, s_b, ob, pw_b, pr_b, sb, s_a, oa, pw_a, pr_a, t_a, sa, vpar, kload_off, None{}, copy_tile, copy_slot);
+  };
+
+  // One round: the eight phases that read tile T (stage STG).  `copy_tile` is T + 1 when that
+  // tile is complete and is to be copied piece by piece during the round, else -1.
+  auto round = [&](auto stg_c, auto first_c, const int copy_tile) __attribute__((always_inline)) {
+    constexpr int STG = decltype(stg_c)::value;
+    constexpr bool FIRST = decltype(first_c)::value;
+    constexpr int so = STG * TILE_BYTES;
+    constexpr int BB = 32 * ROW_BYTES;  // bytes per block
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using O0 = std::integral_constant<int, so>;
+    using O1 = std::integral_constant<int, so + BB>;
+    using O2 = std::integral_constant<int, so + 2 * BB>;
+    using O3 = std::integral_constant<int, so + 3 * BB>;
+    if (FIRST) {
+      // fill: K(0); S_a(0) with V^T(0); S_b(0) with the softmax of s_a(0) and K(1)
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) kf[ks] = lds_read8(kp[ks], so);
+      if (copy_tile >= 0) { copy_piece(copy_tile, 0); copy_piece(copy_tile, 1); }  // the pieces of the phase that has no MFMAs
+      asm_fence();
+      phase_a(Y{}, N{}, N{}, N{}, I1{}, O0{}, copy_tile, I1{});
+      phase_b(Y{}, N{}, Y{}, N{}, I1{}, O1{}, copy_tile, std::integral_constant<int, 2>{});
+    } else {
+      phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, O0{}, copy_tile, I0{});                                  // B(prev 2)
+      phase_a(Y{}, Y{}, Y{}, Y{}, I1{}, O0{}, copy_tile, I1{});                                  // A(prev 3)
+      phase_b(Y{}, Y{}, Y{}, Y{}, I1{}, O1{}, copy_tile, std::integral_constant<int, 2>{});      // B(prev 3)
+    }
+    phase_a(Y{}, Y{}, Y{}, Y{}, I0{}, O1{}, copy_tile, std::integral_constant<int, 3>{});        // A(0)
+    phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, O2{}, copy_tile, std::integral_constant<int, 4>{});        // B(0)
+    phase_a(Y{}, Y{}, Y{}, Y{}, I1{}, O2{}, copy_tile, std::integral_constant<int, 5>{});        // A(1)
+    phase_b(Y{}, Y{}, Y{}, Y{}, I1{}, O3{}, copy_tile, std::integral_constant<int, 6>{});        // B(1)
+    phase_a(Y{}, Y{}, Y{}, Y{}, I0{}, O3{}, copy_tile, std::integral_constant<int, 7>{});        // A(2)
+  };
+  // After a wave's last round: finish blocks 2 and 3 of that tile from registers.
+  auto drain = [&]() __attribute__((always_inline)) {
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, None{}, -1, I0{});   // B(2): S_b(3), PV_b(2), softmax of s_a(3)
+    phase_a(N{}, Y{}, Y{}, Y{}, I1{}, None{}, -1, I0{});   // A(3): PV_a(3), softmax of s_b(3)
+    phase_b(N{}, Y{}, N{}, Y{}, I1{}, None{}, -1, I0{});   // B(3): PV_b(3)
+    mfma_result_fence();
+  };
+
+  // ---- masked tiles: compiler-scheduled, block by block and column block by column block
+  auto generic_block = [&](const bf16x8 (&kfr)[NKS], const bf16x8 (&vtf)[2][NDB], const bf16x8 (&qx)[NKS], f32x16 (&o_x)[NDB],
+                           ColState& st, const int lim) __attribute__((always_inline)) {
+    f32x16 s = mfma_chain_b_in_agpr<NKS>(kfr, qx);
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
+    float mx = s[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    mx = halfwave_max(mx);
+    if (__builtin_amdgcn_ballot_w64(mx > st.thr) != 0) rescale(st, o_x, mx);
+    bf16x8 pf[2];
+#pragma unroll
+    for (int sblk = 0; sblk < 2; ++sblk) {
+      bf16x2 pp[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * sblk + 2 * t], c, st.negmc));
+        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * sblk + 2 * t + 1], c, st.negmc));
+        pp[t] = pack_bf16(e0, e1);
+        st.l += e0 + e1;
+      }
+      pf[sblk] = cat_pairs(pp[0], pp[1], pp[2], pp[3]);
+    }
+#pragma unroll
+    for (int sblk = 0; sblk < 2; ++sblk)
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) o_x[db] = mfma32(vtf[sblk][db], pf[sblk], o_x[db]);
+  };
+  auto generic_tile = [&](const int T) __attribute__((always_inline)) {
+    const int so = (T & 1) * TILE_BYTES;
+    const int kb = T * BN;
+#pragma unroll 1
+    for (int r = 0; r < NB; ++r) {
+      const int key0 = kb + 32 * r;  // first key of the block, relative to k_begin
+      // a block is skipped when no row of the wave can see any of its keys
+      if (key0 >= nk || (p.causal && key0 > wave_row_min + 63)) break;
+      bf16x8 kfr[NKS], vtf[2][NDB];
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) kfr[ks] = lds_read8(kp[ks], so + 32 * r * ROW_BYTES);
+#pragma unroll
+      for (int sblk = 0; sblk < 2; ++sblk)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const int off = so + (32 * r + 16 * sblk) * ROW_BYTES;
+          vtf[sblk][db] = cat4(lds_read_tr4(vp0[db] + off), lds_read_tr4(vp8[db] + off));
+        }
+      // last visible key relative to the lane's first key of the block (keys 4h.. of each 8)
+      const int lim_a = (p.causal ? rel_a : nk - 1) - key0 - 4 * h;
+      const int lim_b = (p.causal ? rel_b : nk - 1) - key0 - 4 * h;
+      if (!(p.causal && key0 > wave_row_min + 31)) generic_block(kfr, vtf, qa, oa, sa, lim_a);
+      generic_block(kfr, vtf, qb, ob, sb, lim_b);
+    }
+  };
+
+  // Leading tiles that need no mask for this wave: complete, and (causal) entirely at or below
+  // the wave's first row.
+  int n_fast = nk / BN;
+  if (p.causal) {
+    const int below = (wave_row_min + 1) / BN;
+    n_fast = n_fast < below ? n_fast : below;
+  }
+
+  agpr_loads_wait();  // Q fragments (and the first tile's copies) have arrived
+  async_wait_all();
+  __syncthreads();
+
+#ifdef IE_EXP_TIMING
+  const unsigned long long t_begin = __builtin_readcyclecounter(), w_begin = wall_clock64();
+  unsigned long long t_sync = 0, t_fast = 0;
+#endif
+  auto end_of_tile = [&]() __attribute__((always_inline)) {
+#ifdef IE_EXP_TIMING
+    const unsigned long long ts0 = __builtin_readcyclecounter();
+#endif
+    async_wait_all();  // this wave's copies of the next tile have landed ...
+    __syncthreads();   // ... everyone's have, and everyone is done reading this stage
+#ifdef IE_EXP_TIMING
+    t_sync += __builtin_readcyclecounter() - ts0;
+#endif
+  };
+  // Starts the copy of tile T + 1 unless it is left to the round (a complete tile, piece by
+  // piece); returns the tile the round has to copy, or -1.
+  auto next_copy = [&](const int T) __attribute__((always_inline)) {
+    const bool next_full = (T + 2) * BN <= nk;
+    if (!next_full && T + 1 < nkt) copy_all(T + 1);
+    return next_full ? T + 1 : -1;
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  int T = 0;
+  if (n_fast > 0) {
+    round(S0{}, Y{}, next_copy(0));
+    end_of_tile();
+    // steady state, two rounds per trip so that the stage offsets are compile-time constants
+    for (T = 1; T + 1 < n_fast; T += 2) {
+      round(S1{}, N{}, next_copy(T));
+      end_of_tile();
+      round(S0{}, N{}, next_copy(T + 1));
+      end_of_tile();
+    }
+    if (T < n_fast) {
+      round(S1{}, N{}, next_copy(T));
+      end_of_tile();
+      ++T;
+    }
+    drain();
+  }
+#ifdef IE_EXP_TIMING
+  t_fast = __builtin_readcyclecounter() - t_begin;
+#endif
+  for (; T < nkt; ++T) {
+    if (T + 1 < nkt) copy_all(T + 1);
+    generic_tile(T);
+    end_of_tile();
+  }
+  mfma_result_fence();
+
+  // Epilogue: normalise, write O (bf16) and LSE (natural log).
+  auto store = [&](const f32x16 (&o)[NDB], const ColState& st, const int64_t row, const bool ok) __attribute__((always_inline)) {
+    const float l_full = halfwave_sum(st.l);
+    const float inv_l = 1.0f / l_full;
+    if (ok) {
+      __bf16* orow = p.o_out + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D + row * q_stride;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          bf16x4 w;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) w[t] = (__bf16)(o[db][4 * q4 + t] * inv_l);
+          *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * q4 + 4 * h) = w;
+        }
+#ifndef IE_EXP_TIMING
+      if (h == 0) p.lse_out[((int64_t)tc.b * p.Hq + tc.h) * p.S + row] = (st.m * c + __builtin_amdgcn_logf(l_full)) * kLn2;
+#endif
+    }
+  };
+  store(oa, sa, row_a, ok_a);
+  store(ob, sb, row_b, ok_b);
+#ifdef IE_EXP_TIMING
+  if (lane == 0) {  // timing build: the lse buffer carries per-wave counters instead
+    unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.lse_out) + ((size_t)blockIdx.x * 4 + wv) * 8;
+    dbg[0] = __builtin_readcyclecounter() - t_begin;
+    dbg[1] = wall_clock64() - w_begin;
+    dbg[2] = nkt; dbg[3] = n_fast; dbg[4] = t_sync; dbg[5] = t_fast;
+  }
+#endif
+}
+
+int launch_fwd_wide(AttnParams p, hipStream_t st) {
+  constexpr int smem = FwdWideCfg::SMEM_BYTES;
+  int rc = set_smem(attn_fwd_wide_kernel, smem);
+  if (rc) return rc;
+  int64_t tiles = tiles_per_head(p.S, FwdWideCfg::BM, p.cu, p.num_docs);
+  int64_t grid = tiles * p.B * p.Hq;
+  if (grid >= ((int64_t)1 << 31)) return kErrShape;
+  p.tiles = (int32_t)tiles;
+  attn_fwd_wide_kernel<<<dim3((unsigned)grid), dim3(kThreads), smem, st>>>(p);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? 0 : hip_fail(e);
+}
+
+}  // namespace ie

@@ -11,6 +11,7 @@ namespace ie {
 int hip_fail(hipError_t e);
 
 int launch_fwd(AttnParams p, int D, hipStream_t st);
+int launch_fwd_wide(AttnParams p, hipStream_t st);  // head dimension 128
 // phases: bit 0 delta, bit 1 dq, bit 2 dk/dv
 int launch_bwd(AttnParams p, int D, int phases, hipStream_t st);
 

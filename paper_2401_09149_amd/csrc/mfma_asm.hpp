@@ -87,6 +87,47 @@ __device__ __forceinline__ void pack_pair(uint32_t& packed, float a, float b) {
   asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(packed) : "v"(a), "v"(b));
 }
 
+// ---- row maximum of a 32x32 C block held as one column per lane (forward softmax) -----------
+// t = max(s[0..8]) / t = max(t, s[9..15]): two groups of four instructions
+template <bool LEAD>
+__device__ __forceinline__ void colmax_lo(float& t, const f32x16& s) {
+  if (LEAD) asm volatile("s_nop 9");
+  asm volatile(
+      "v_max3_f32 %0, %1, %2, %3\n\t"
+      "v_max3_f32 %0, %0, %4, %5\n\t"
+      "v_max3_f32 %0, %0, %6, %7\n\t"
+      "v_max3_f32 %0, %0, %8, %9"
+      : "=&v"(t)
+      : "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]), "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]), "v"(s[8]));
+}
+__device__ __forceinline__ void colmax_hi(float& t, const f32x16& s) {
+  asm volatile(
+      "v_max3_f32 %0, %0, %1, %2\n\t"
+      "v_max3_f32 %0, %0, %3, %4\n\t"
+      "v_max3_f32 %0, %0, %5, %6\n\t"
+      "v_max_f32 %0, %0, %7"
+      : "+v"(t)
+      : "v"(s[9]), "v"(s[10]), "v"(s[11]), "v"(s[12]), "v"(s[13]), "v"(s[14]), "v"(s[15]));
+}
+// t = max(t, t of the lane 32 away): the two half-waves hold the two halves of a column
+__device__ __forceinline__ void halfwave_max_asm(float& t) {
+  float u;
+  asm volatile(
+      "v_mov_b32 %1, %0\n\t"
+      "s_nop 1\n\t"
+      "v_permlane32_swap_b32 %0, %1\n\t"
+      "v_max_f32 %0, %0, %1"
+      : "+v"(t), "=&v"(u));
+}
+// p = exp2(s*c + negmc)
+__device__ __forceinline__ void exp_elem(float& p, float s, float c, float negmc) {
+  asm volatile("v_fma_f32 %0, %1, %2, %3\n\tv_exp_f32 %0, %0" : "=&v"(p) : "v"(s), "s"(c), "v"(negmc));
+}
+// l += p.  When p comes from v_exp_f32, at least one other instruction must have been issued since.
+__device__ __forceinline__ void add_to(float& l, float p) {
+  asm volatile("v_add_f32 %0, %0, %1" : "+v"(l) : "v"(p));
+}
+
 __device__ __forceinline__ bf16x8 frag_from_words(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
   u32x4 w = {a, b, c, d};
   return __builtin_bit_cast(bf16x8, w);
