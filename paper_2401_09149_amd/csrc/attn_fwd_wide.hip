@@ -97,12 +97,27 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
       ld.load(base + V_BASE + part * C::PART_BYTES, vbase + T * tile_pitch + (int64_t)first * kv_pitch, valid);
     }
   };
-  auto copy_piece = [&](const int T, const int k) __attribute__((always_inline)) {
-    constexpr int NI = AsyncTile<D>::NI, RPI = AsyncTile<D>::RPI;
+  // Piece k of a complete tile: instruction i of 64-row part `part` of tensor `tensor`.  The row
+  // offset of the instruction sits in a per-lane offset register and the part's in the scalar base,
+  // so that a piece costs three instructions (M0, a wait state, the copy).
+  uint32_t voff_i[AsyncTile<D>::NI];
+#pragma unroll
+  for (int i = 0; i < AsyncTile<D>::NI; ++i) voff_i[i] = ld.voff + (uint32_t)(4 * AsyncTile<D>::RPI * i) * ld.pitch;
+  struct CopySrc { const char* k[BN / 64]; const char* v[BN / 64]; uint32_t lds; };
+  auto copy_src = [&](const int T) __attribute__((always_inline)) {
+    CopySrc cs;
+#pragma unroll
+    for (int part = 0; part < BN / 64; ++part) {
+      cs.k[part] = kbase + T * tile_pitch + (int64_t)(64 * part) * kv_pitch;
+      cs.v[part] = vbase + T * tile_pitch + (int64_t)(64 * part) * kv_pitch;
+    }
+    cs.lds = lds0 + (T & 1) * TILE_BYTES + wave_u * 1024;
+    return cs;
+  };
+  auto copy_piece = [&](const CopySrc& cs, const int k) __attribute__((always_inline)) {
+    constexpr int NI = AsyncTile<D>::NI;
     const int tensor = k / ((BN / 64) * NI), part = (k / NI) % (BN / 64), i = k % NI;
-    const int row = 64 * part + 4 * RPI * i;
-    async_copy16(ld.voff, (tensor ? vbase : kbase) + T * tile_pitch + (int64_t)row * kv_pitch,
-                 lds0 + (T & 1) * TILE_BYTES + tensor * V_BASE + part * C::PART_BYTES + (i * 4 + wave_u) * 1024);
+    async_copy16(voff_i[i], tensor ? cs.v[part] : cs.k[part], cs.lds + tensor * V_BASE + part * C::PART_BYTES + i * 4096);
   };
   copy_all(0);
 
@@ -178,9 +193,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   // Element e of a softmax: its exponential; the sum takes the previous element and the pack the
   // previous pair, so that neither reads a v_exp_f32 result in the very next instruction.
   auto elem = [&](float (&pr)[16], uint32_t (&pw)[8], const f32x16& s, ColState& st, const int e) __attribute__((always_inline)) {
-    exp_elem(pr[e], s[e], c, st.negmc);
-    if (e >= 1) add_to(st.l, pr[e - 1]);
-    if (e >= 2 && (e & 1) == 0) pack_pair(pw[e / 2 - 1], pr[e - 2], pr[e - 1]);
+    if (e == 0) exp_elem(pr[0], s[0], c, st.negmc);
+    else if (e & 1) exp_elem_add(pr[e], s[e], c, st.negmc, st.l, pr[e - 1]);
+    else exp_elem_add_pack(pr[e], s[e], c, st.negmc, st.l, pr[e - 1], pw[e / 2 - 1], pr[e - 2]);
   };
 
   // One phase: 16 MFMA slots.  X is the column block whose MFMAs run (S of block i+1 on even
@@ -191,17 +206,26 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   auto phase = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, const bf16x8 (&qx)[NKS], f32x16& s_x,
                    f32x16 (&o_x)[NDB], uint32_t (&pw_x)[8], float (&pr_x)[16], ColState& st_x, f32x16& s_y,
                    f32x16 (&o_y)[NDB], uint32_t (&pw_y)[8], float (&pr_y)[16], float& t_y, ColState& st_y, auto vpar_c,
-                   auto kload_c, auto vload_c, const int copy_tile, auto slot_c)
+                   auto kload_c, auto vload_c, const bool copying, const CopySrc& cs, auto slot_c)
       __attribute__((always_inline)) {
     constexpr bool HAS_S = decltype(has_s)::value, HAS_PV = decltype(has_pv)::value;
+#ifdef IE_EXP_W_NOSM
+    constexpr bool HAS_SM = false, HAS_TAIL = false;
+#else
     constexpr bool HAS_SM = decltype(has_sm)::value, HAS_TAIL = decltype(has_tail)::value;
+#endif
+#ifdef IE_EXP_W_NOLDS
+    constexpr int vpar = decltype(vpar_c)::value, kload_off = -1, vload_off = -1;
+#else
     constexpr int vpar = decltype(vpar_c)::value, kload_off = decltype(kload_c)::value;
-    constexpr int vload_off = decltype(vload_c)::value, copy_slot = decltype(slot_c)::value;
+    constexpr int vload_off = decltype(vload_c)::value;
+#endif
+    constexpr int copy_slot = decltype(slot_c)::value;
     bf16x8 pf0, pf1;
 #pragma unroll
     for (int pos = 0; pos < 16; ++pos) {
       const int k = pos >> 1;
-      if (copy_tile >= 0 && (pos == 0 || pos == 8)) copy_piece(copy_tile, 2 * copy_slot + (pos >> 3));
+      if (copying && (pos == 0 || pos == 8)) copy_piece(cs, 2 * copy_slot + (pos >> 3));
       // ---- the MFMA of this slot, and the LDS read that can follow it
       if ((pos & 1) == 0) {
         if (HAS_S) {
@@ -222,8 +246,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
       }
       // ---- the VALU work of this slot
       if (HAS_TAIL && pos == 0) {
-        add_to(st_x.l, pr_x[15]);
-        pack_pair(pw_x[7], pr_x[14], pr_x[15]);
+        add_pack(st_x.l, pr_x[15], pw_x[7], pr_x[14]);
       }
       if (HAS_SM) {
         if (pos == 1) colmax_lo<true>(t_y, s_y);
@@ -243,18 +266,26 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   using Y = std::true_type;
   using N = std::false_type;
   using None = std::integral_constant<int, -1>;
-  auto phase_a = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, auto vpar, auto vload_off, int copy_tile, auto copy_slot)
+  bool copying = false;  // the current round copies the next tile piece by piece
+  CopySrc cs{};
+  auto phase_a = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, auto vpar, auto vload_off, auto copy_slot)
       __attribute__((always_inline)) {
-    phase(has_s, has_pv, has_sm, has_tail, qa, s_a, oa, pw_a, pr_a, sa, s_b, ob, pw_b, pr_b, t_b, sb, vpar, None{}, vload_off, copy_tile, copy_slot);
+    phase(has_s, has_pv, has_sm, has_tail, qa, s_a, oa, pw_a, pr_a, sa, s_b, ob, pw_b, pr_b, t_b, sb, vpar, None{}, vload_off, copying, cs, copy_slot);
   };
-  auto phase_b = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, auto vpar, auto kload_off, int copy_tile, auto copy_slot)
+  auto phase_b = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, auto vpar, auto kload_off, auto copy_slot)
       __attribute__((always_inline)) {
-    phase(has_s, has_pv, has_sm, has_tail, qb, s_b, ob, pw_b, pr_b, sb, s_a, oa, pw_a, pr_a, t_a, sa, vpar, kload_off, None{}, copy_tile, copy_slot);
+    phase(has_s, has_pv, has_sm, has_tail, qb, s_b, ob, pw_b, pr_b, sb, s_a, oa, pw_a, pr_a, t_a, sa, vpar, kload_off, None{}, copying, cs, copy_slot);
   };
 
   // One round: the eight phases that read tile T (stage STG).  `copy_tile` is T + 1 when that
   // tile is complete and is to be copied piece by piece during the round, else -1.
   auto round = [&](auto stg_c, auto first_c, const int copy_tile) __attribute__((always_inline)) {
+#ifdef IE_EXP_W_NOCOPY
+    copying = false;
+#else
+    copying = copy_tile >= 0;
+#endif
+    if (copying) cs = copy_src(copy_tile);
     constexpr int STG = decltype(stg_c)::value;
     constexpr bool FIRST = decltype(first_c)::value;
     constexpr int so = STG * TILE_BYTES;
@@ -269,28 +300,29 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
       // fill: K(0); S_a(0) with V^T(0); S_b(0) with the softmax of s_a(0) and K(1)
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) kf[ks] = lds_read8(kp[ks], so);
-      if (copy_tile >= 0) { copy_piece(copy_tile, 0); copy_piece(copy_tile, 1); }  // the pieces of the phase that has no MFMAs
+      if (copying) { copy_piece(cs, 0); copy_piece(cs, 1); }  // the pieces of the phase that has no MFMAs
       asm_fence();
-      phase_a(Y{}, N{}, N{}, N{}, I1{}, O0{}, copy_tile, I1{});
-      phase_b(Y{}, N{}, Y{}, N{}, I1{}, O1{}, copy_tile, std::integral_constant<int, 2>{});
+      phase_a(Y{}, N{}, N{}, N{}, I1{}, O0{}, I1{});
+      phase_b(Y{}, N{}, Y{}, N{}, I1{}, O1{}, std::integral_constant<int, 2>{});
     } else {
-      phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, O0{}, copy_tile, I0{});                                  // B(prev 2)
-      phase_a(Y{}, Y{}, Y{}, Y{}, I1{}, O0{}, copy_tile, I1{});                                  // A(prev 3)
-      phase_b(Y{}, Y{}, Y{}, Y{}, I1{}, O1{}, copy_tile, std::integral_constant<int, 2>{});      // B(prev 3)
+      phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, O0{}, I0{});                                  // B(prev 2)
+      phase_a(Y{}, Y{}, Y{}, Y{}, I1{}, O0{}, I1{});                                  // A(prev 3)
+      phase_b(Y{}, Y{}, Y{}, Y{}, I1{}, O1{}, std::integral_constant<int, 2>{});      // B(prev 3)
     }
-    phase_a(Y{}, Y{}, Y{}, Y{}, I0{}, O1{}, copy_tile, std::integral_constant<int, 3>{});        // A(0)
-    phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, O2{}, copy_tile, std::integral_constant<int, 4>{});        // B(0)
-    phase_a(Y{}, Y{}, Y{}, Y{}, I1{}, O2{}, copy_tile, std::integral_constant<int, 5>{});        // A(1)
-    phase_b(Y{}, Y{}, Y{}, Y{}, I1{}, O3{}, copy_tile, std::integral_constant<int, 6>{});        // B(1)
-    phase_a(Y{}, Y{}, Y{}, Y{}, I0{}, O3{}, copy_tile, std::integral_constant<int, 7>{});        // A(2)
+    phase_a(Y{}, Y{}, Y{}, Y{}, I0{}, O1{}, std::integral_constant<int, 3>{});        // A(0)
+    phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, O2{}, std::integral_constant<int, 4>{});        // B(0)
+    phase_a(Y{}, Y{}, Y{}, Y{}, I1{}, O2{}, std::integral_constant<int, 5>{});        // A(1)
+    phase_b(Y{}, Y{}, Y{}, Y{}, I1{}, O3{}, std::integral_constant<int, 6>{});        // B(1)
+    phase_a(Y{}, Y{}, Y{}, Y{}, I0{}, O3{}, std::integral_constant<int, 7>{});        // A(2)
   };
   // After a wave's last round: finish blocks 2 and 3 of that tile from registers.
   auto drain = [&]() __attribute__((always_inline)) {
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, None{}, -1, I0{});   // B(2): S_b(3), PV_b(2), softmax of s_a(3)
-    phase_a(N{}, Y{}, Y{}, Y{}, I1{}, None{}, -1, I0{});   // A(3): PV_a(3), softmax of s_b(3)
-    phase_b(N{}, Y{}, N{}, Y{}, I1{}, None{}, -1, I0{});   // B(3): PV_b(3)
+    copying = false;
+    phase_b(Y{}, Y{}, Y{}, Y{}, I0{}, None{}, I0{});   // B(2): S_b(3), PV_b(2), softmax of s_a(3)
+    phase_a(N{}, Y{}, Y{}, Y{}, I1{}, None{}, I0{});   // A(3): PV_a(3), softmax of s_b(3)
+    phase_b(N{}, Y{}, N{}, Y{}, I1{}, None{}, I0{});   // B(3): PV_b(3)
     mfma_result_fence();
   };
 
@@ -358,9 +390,21 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
     n_fast = n_fast < below ? n_fast : below;
   }
 
+  // The four waves run the same instruction sequence; released together by the barrier they would
+  // reach every copy instruction in the same cycle and queue in the CU's one vector-memory path
+  // (about 16 cycles per instruction), holding back the MFMAs behind.  A delay of 20 cycles per
+  // wave index after each barrier keeps them apart for the whole round.
+  auto stagger = [&]() __attribute__((always_inline)) {
+#ifndef IE_EXP_W_NOSTAGGER
+    if (wave_u >= 1) asm volatile("s_nop 15\n\ts_nop 3");
+    if (wave_u >= 2) asm volatile("s_nop 15\n\ts_nop 3");
+    if (wave_u >= 3) asm volatile("s_nop 15\n\ts_nop 3");
+#endif
+  };
   agpr_loads_wait();  // Q fragments (and the first tile's copies) have arrived
   async_wait_all();
   __syncthreads();
+  stagger();
 
 #ifdef IE_EXP_TIMING
   const unsigned long long t_begin = __builtin_readcyclecounter(), w_begin = wall_clock64();
@@ -372,6 +416,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
 #endif
     async_wait_all();  // this wave's copies of the next tile have landed ...
     __syncthreads();   // ... everyone's have, and everyone is done reading this stage
+    stagger();
 #ifdef IE_EXP_TIMING
     t_sync += __builtin_readcyclecounter() - ts0;
 #endif

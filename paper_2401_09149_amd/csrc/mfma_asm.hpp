@@ -119,13 +119,26 @@ __device__ __forceinline__ void halfwave_max_asm(float& t) {
       "v_max_f32 %0, %0, %1"
       : "+v"(t), "=&v"(u));
 }
-// p = exp2(s*c + negmc)
+// One element of the forward softmax, as one block so that the compiler puts nothing between its
+// instructions: p = exp2(s*c + negmc); then, with the PREVIOUS elements (whose v_exp_f32 results
+// are by now at least one instruction old): l += p_prev, and packed = {bf16(p_prev2), bf16(p_prev)}.
 __device__ __forceinline__ void exp_elem(float& p, float s, float c, float negmc) {
   asm volatile("v_fma_f32 %0, %1, %2, %3\n\tv_exp_f32 %0, %0" : "=&v"(p) : "v"(s), "s"(c), "v"(negmc));
 }
-// l += p.  When p comes from v_exp_f32, at least one other instruction must have been issued since.
-__device__ __forceinline__ void add_to(float& l, float p) {
-  asm volatile("v_add_f32 %0, %0, %1" : "+v"(l) : "v"(p));
+__device__ __forceinline__ void exp_elem_add(float& p, float s, float c, float negmc, float& l, float p_prev) {
+  asm volatile("v_fma_f32 %0, %2, %3, %4\n\tv_exp_f32 %0, %0\n\tv_add_f32 %1, %1, %5"
+               : "=&v"(p), "+v"(l)
+               : "v"(s), "s"(c), "v"(negmc), "v"(p_prev));
+}
+__device__ __forceinline__ void exp_elem_add_pack(float& p, float s, float c, float negmc, float& l, float p_prev,
+                                                  uint32_t& packed, float p_prev2) {
+  asm volatile("v_fma_f32 %0, %3, %4, %5\n\tv_exp_f32 %0, %0\n\tv_add_f32 %1, %1, %6\n\tv_cvt_pk_bf16_f32 %2, %7, %6"
+               : "=&v"(p), "+v"(l), "=v"(packed)
+               : "v"(s), "s"(c), "v"(negmc), "v"(p_prev), "v"(p_prev2));
+}
+// The last element's sum and pack (one MFMA later).
+__device__ __forceinline__ void add_pack(float& l, float p_prev, uint32_t& packed, float p_prev2) {
+  asm volatile("v_add_f32 %0, %0, %2\n\tv_cvt_pk_bf16_f32 %1, %3, %2" : "+v"(l), "=v"(packed) : "v"(p_prev), "v"(p_prev2));
 }
 
 __device__ __forceinline__ bf16x8 frag_from_words(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
