@@ -149,6 +149,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
 
   const float c = p.scale_log2;
   constexpr float kSlack = 8.0f;  // log2 units, see attn_fwd.hip
+  // The hand-sequenced path lets exponentials grow much further before it moves the reference:
+  // a block is done again only if one lane's 16 exponentials sum to more than this (or to NaN).
+  // Probabilities up to 2^24 against a reference that lags are harmless in fp32 and in bf16 (both
+  // keep 8 exponent bits): the final normalisation by l removes the common factor.
+  constexpr float kRedo = 16777216.0f;
   const float slack_raw = kSlack / c;
   ColState sa{-INFINITY, INFINITY, -INFINITY, 0.f}, sb{-INFINITY, INFINITY, -INFINITY, 0.f};
   f32x16 oa[NDB], ob[NDB];  // live in AGPRs
@@ -188,14 +193,34 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   f32x16 s_a, s_b;         // scores of the current block of each column block
   uint32_t pw_a[8], pw_b[8];  // packed probabilities (bf16 pairs) of each column block
   float pr_a[16], pr_b[16];   // exponentials waiting to be summed and packed
-  float t_a, t_b;             // running column maxima
+  float lsum_a, lsum_b;       // this lane's sum of the current block's exponentials
 
-  // Element e of a softmax: its exponential; the sum takes the previous element and the pack the
-  // previous pair, so that neither reads a v_exp_f32 result in the very next instruction.
-  auto elem = [&](float (&pr)[16], uint32_t (&pw)[8], const f32x16& s, ColState& st, const int e) __attribute__((always_inline)) {
-    if (e == 0) exp_elem(pr[0], s[0], c, st.negmc);
-    else if (e & 1) exp_elem_add(pr[e], s[e], c, st.negmc, st.l, pr[e - 1]);
-    else exp_elem_add_pack(pr[e], s[e], c, st.negmc, st.l, pr[e - 1], pw[e / 2 - 1], pr[e - 2]);
+  // Element e of a block's softmax: its exponential; the block sum takes the previous element and
+  // the pack the previous pair, so that neither reads a v_exp_f32 result in the very next instruction.
+  auto elem = [&](float (&pr)[16], uint32_t (&pw)[8], const f32x16& s, const ColState& st, float& lsum, const int e)
+      __attribute__((always_inline)) {
+    if (e < 2) exp_elem(pr[e], s[e], c, st.negmc);
+    else if (e == 2) exp_elem_first_sum(pr[2], s[2], c, st.negmc, lsum, pr[0], pr[1], pw[0]);
+    else if (e & 1) exp_elem_add(pr[e], s[e], c, st.negmc, lsum, pr[e - 1]);
+    else exp_elem_add_pack(pr[e], s[e], c, st.negmc, lsum, pr[e - 1], pw[e / 2 - 1], pr[e - 2]);
+  };
+  // A block whose exponentials outgrew the reference (or the very first block of a row): find
+  // the true column maximum, move the reference there and form the block's probabilities again.
+  // Cold: after its first blocks a row practically never comes here.
+  auto redo = [&](ColState& st, f32x16 (&o)[NDB], const f32x16& s, uint32_t (&pw)[8], float& lsum) __attribute__((always_inline)) {
+    float mx = s[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    mx = halfwave_max(mx);
+    rescale(st, o, mx);
+    lsum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * t], c, st.negmc));
+      const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * t + 1], c, st.negmc));
+      pw[t] = __builtin_bit_cast(uint32_t, pack_bf16(e0, e1));
+      lsum += e0 + e1;
+    }
   };
 
   // One phase: 16 MFMA slots.  X is the column block whose MFMAs run (S of block i+1 on even
@@ -205,14 +230,14 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   // TAIL: X's previous softmax left its last sum and pack for slot 0.
   auto phase = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, const bf16x8 (&qx)[NKS], f32x16& s_x,
                    f32x16 (&o_x)[NDB], uint32_t (&pw_x)[8], float (&pr_x)[16], ColState& st_x, f32x16& s_y,
-                   f32x16 (&o_y)[NDB], uint32_t (&pw_y)[8], float (&pr_y)[16], float& t_y, ColState& st_y, auto vpar_c,
+                   f32x16 (&o_y)[NDB], uint32_t (&pw_y)[8], float (&pr_y)[16], float& lsum_y, ColState& st_y, auto vpar_c,
                    auto kload_c, auto vload_c, const bool copying, const CopySrc& cs, auto slot_c)
       __attribute__((always_inline)) {
     constexpr bool HAS_S = decltype(has_s)::value, HAS_PV = decltype(has_pv)::value;
 #ifdef IE_EXP_W_NOSM
-    constexpr bool HAS_SM = false, HAS_TAIL = false;
+    constexpr bool HAS_SM = false;
 #else
-    constexpr bool HAS_SM = decltype(has_sm)::value, HAS_TAIL = decltype(has_tail)::value;
+    constexpr bool HAS_SM = decltype(has_sm)::value;
 #endif
 #ifdef IE_EXP_W_NOLDS
     constexpr int vpar = decltype(vpar_c)::value, kload_off = -1, vload_off = -1;
@@ -244,20 +269,18 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
           vt[vpar ^ 1][k / NDB][k % NDB] = cat4(lds_read_tr4(vp0[k % NDB] + off), lds_read_tr4(vp8[k % NDB] + off));
         }
       }
-      // ---- the VALU work of this slot
-      if (HAS_TAIL && pos == 0) {
-        add_pack(st_x.l, pr_x[15], pw_x[7], pr_x[14]);
-      }
+      // ---- the VALU work of this slot: the softmax of s_y.  Its scores were complete four MFMAs
+      // before slot 2.  There is no running maximum: the exponentials are taken against the
+      // column's current reference, and only a block whose sum shows that the reference is too
+      // low (or not set yet) is done again.
       if (HAS_SM) {
-        if (pos == 1) colmax_lo<true>(t_y, s_y);
-        if (pos == 2) colmax_hi(t_y, s_y);
-        if (pos == 3) {
-          halfwave_max_asm(t_y);
-          if (__builtin_amdgcn_ballot_w64(t_y > st_y.thr) != 0) rescale(st_y, o_y, t_y);
+        if (pos >= 2 && pos <= 4) { elem(pr_y, pw_y, s_y, st_y, lsum_y, 2 * (pos - 2)); elem(pr_y, pw_y, s_y, st_y, lsum_y, 2 * (pos - 2) + 1); }
+        if (pos >= 5 && pos <= 14) elem(pr_y, pw_y, s_y, st_y, lsum_y, pos + 1);
+        if (pos == 15) {
+          add_pack(lsum_y, pr_y[15], pw_y[7], pr_y[14]);
+          if (__builtin_amdgcn_ballot_w64(!(lsum_y <= kRedo)) != 0) redo(st_y, o_y, s_y, pw_y, lsum_y);
+          st_y.l += lsum_y;
         }
-        // slots 4..7 take two elements each (0..7), slots 8..15 one each (8..15)
-        if (pos >= 4 && pos < 8) { elem(pr_y, pw_y, s_y, st_y, 2 * (pos - 4)); elem(pr_y, pw_y, s_y, st_y, 2 * (pos - 4) + 1); }
-        if (pos >= 8) elem(pr_y, pw_y, s_y, st_y, pos);
       }
       asm_fence();
     }
@@ -270,11 +293,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   CopySrc cs{};
   auto phase_a = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, auto vpar, auto vload_off, auto copy_slot)
       __attribute__((always_inline)) {
-    phase(has_s, has_pv, has_sm, has_tail, qa, s_a, oa, pw_a, pr_a, sa, s_b, ob, pw_b, pr_b, t_b, sb, vpar, None{}, vload_off, copying, cs, copy_slot);
+    phase(has_s, has_pv, has_sm, has_tail, qa, s_a, oa, pw_a, pr_a, sa, s_b, ob, pw_b, pr_b, lsum_b, sb, vpar, None{}, vload_off, copying, cs, copy_slot);
   };
   auto phase_b = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, auto vpar, auto kload_off, auto copy_slot)
       __attribute__((always_inline)) {
-    phase(has_s, has_pv, has_sm, has_tail, qb, s_b, ob, pw_b, pr_b, sb, s_a, oa, pw_a, pr_a, t_a, sa, vpar, kload_off, None{}, copying, cs, copy_slot);
+    phase(has_s, has_pv, has_sm, has_tail, qb, s_b, ob, pw_b, pr_b, sb, s_a, oa, pw_a, pr_a, lsum_a, sa, vpar, kload_off, None{}, copying, cs, copy_slot);
   };
 
   // One round: the eight phases that read tile T (stage STG).  `copy_tile` is T + 1 when that

@@ -136,6 +136,13 @@ __device__ __forceinline__ void exp_elem_add_pack(float& p, float s, float c, fl
                : "=&v"(p), "+v"(l), "=v"(packed)
                : "v"(s), "s"(c), "v"(negmc), "v"(p_prev), "v"(p_prev2));
 }
+// Element 2 opens the block's sum: lsum = p0 + p1.
+__device__ __forceinline__ void exp_elem_first_sum(float& p, float s, float c, float negmc, float& lsum, float p0, float p1,
+                                                   uint32_t& packed) {
+  asm volatile("v_fma_f32 %0, %3, %4, %5\n\tv_exp_f32 %0, %0\n\tv_add_f32 %1, %6, %7\n\tv_cvt_pk_bf16_f32 %2, %6, %7"
+               : "=&v"(p), "=&v"(lsum), "=v"(packed)
+               : "v"(s), "s"(c), "v"(negmc), "v"(p0), "v"(p1));
+}
 // The last element's sum and pack (one MFMA later).
 __device__ __forceinline__ void add_pack(float& l, float p_prev, uint32_t& packed, float p_prev2) {
   asm volatile("v_add_f32 %0, %0, %2\n\tv_cvt_pk_bf16_f32 %1, %3, %2" : "+v"(l), "=v"(packed) : "v"(p_prev), "v"(p_prev2));
