@@ -79,7 +79,7 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the workload table (default: the headline config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-prefix", type=int, default=32768)
-    ap.add_argument("--cpu-heads", type=int, default=2)
+    ap.add_argument("--cpu-heads", type=int, default=1)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -152,7 +152,7 @@ def main():
     # already counted in the dK/dV kernel.  Pairs are counted as L^2/2 per document.
     pairs = f_fwd / (4.0 * cfg.D)   # = B * Hq * sum L^2 / 2
     kernels = {
-        "attn_fwd_kernel": (fwd_ms, 4.0 * cfg.D * pairs),
+        ("attn_fwd_wide_kernel" if cfg.D == 128 else "attn_fwd_kernel"): (fwd_ms, 4.0 * cfg.D * pairs),
         "attn_bwd_dkdv_kernel": (dkdv_ms, 8.0 * cfg.D * pairs),
         "attn_bwd_dq_kernel": (dq_ms, 6.0 * cfg.D * pairs),
     }
