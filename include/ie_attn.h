@@ -70,8 +70,8 @@ int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
                 float scale, int32_t causal, void* stream);
 
 /*
- * Bytes of device workspace ie_attn_bwd needs for this shape (it holds delta and
- * lse * log2(e), [B,Hq,S] fp32 each, between the kernels of one call).  Returns 0 for an invalid shape.  Pure host
+ * Bytes of device workspace ie_attn_bwd needs for this shape (it holds -delta and
+ * -lse * log2(e), [B,Hq,S] fp32 each, between the kernels of one call).  Returns 0 for an invalid shape.  Pure host
  * arithmetic; touches no device.
  */
 size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs);
@@ -95,7 +95,7 @@ int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
 /*
  * The same backward pass, restricted to some of its kernels, for profilers and benchmarks
  * that time one kernel at a time.  `phases` is a bit mask: IE_BWD_DELTA (delta = rowsum(dO o O)
- * and lse * log2(e) into the workspace), IE_BWD_DQ (writes dq; needs what IE_BWD_DELTA left in the
+ * and lse * log2(e), both negated, into the workspace), IE_BWD_DQ (writes dq; needs what IE_BWD_DELTA left in the
  * workspace), IE_BWD_DKDV (writes dk and dv; needs the same).  Outputs of phases that are not selected are left
  * untouched.  ie_attn_bwd(...) is ie_attn_bwd_phases(..., IE_BWD_ALL).  A mask of 0 or with
  * other bits set is IE_ERR_UNSUPPORTED.

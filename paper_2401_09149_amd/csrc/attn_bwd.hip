@@ -232,7 +232,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
 // ---- dK, dV ------------------------------------------------------------------------------
 // One workgroup per (batch, kv head, 128 keys); wave w owns keys 32w..32w+31 and keeps their
 // K and V fragments and the dK^T / dV^T accumulators in registers for the whole kernel.
-// Query tiles of 64 rows (Q, dO, lse*log2e, delta) stream through a ring of LDS stages
+// Query tiles of 128 rows (Q, dO, -lse*log2e, -delta) stream through two LDS stages
 // filled by asynchronous copies; all query heads of the kv head's group pass through the
 // same accumulators, which is the GQA reduction.
 template <int D>

@@ -38,7 +38,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 struct AttnParams {
   const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* dout;
   __bf16* o_out; float* lse_out;
-  const float* lse; float* delta; float* lse2;  // lse2 = lse * log2(e), written by the delta kernel
+  const float* lse; float* delta; float* lse2;  // workspace, written by the delta kernel: -delta and -lse * log2(e)
   __bf16* dq; __bf16* dk; __bf16* dv;
   const int32_t* cu; int32_t num_docs;
   int64_t B, S;

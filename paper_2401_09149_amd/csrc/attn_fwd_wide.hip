@@ -9,7 +9,7 @@
 // column block.
 //
 // Unmasked tiles run a hand-sequenced pipeline (mfma_asm.hpp).  The softmax of a 32x32 block is
-// about 70 VALU instructions against 16 MFMAs, more than fits in the MFMAs' shadow if the two
+// about 57 VALU instructions against 16 MFMAs, more than fits in the MFMAs' shadow if the two
 // are not interleaved instruction by instruction, so the two column blocks are staggered by
 // half a block and each phase pairs the MFMAs of one with the softmax of the other
 // (i = 32-key block index):
@@ -227,7 +227,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   // slots, PV of block i on odd slots), Y the one whose softmax runs (on s_y).  KLOAD / VLOAD: after a
   // K fragment's last use load the next block's (r = local block index in stage STG, or -1);
   // load the next block's V^T into the other buffer.
-  // TAIL: X's previous softmax left its last sum and pack for slot 0.
   auto phase = [&](auto has_s, auto has_pv, auto has_sm, auto has_tail, const bf16x8 (&qx)[NKS], f32x16& s_x,
                    f32x16 (&o_x)[NDB], uint32_t (&pw_x)[8], float (&pr_x)[16], ColState& st_x, f32x16& s_y,
                    f32x16 (&o_y)[NDB], uint32_t (&pw_y)[8], float (&pr_y)[16], float& lsum_y, ColState& st_y, auto vpar_c,
