@@ -83,6 +83,73 @@ def test_large_scores_stay_finite(oracle):
     case(oracle, 1, 513, 2, 2, 128, seed=91, scale=4 * 128 ** -0.5, grad_abs_tol=4 * 5e-2)
 
 
+@pytest.mark.parametrize("S", [255, 256, 257, 384, 385, 511, 512, 769])
+def test_lengths_around_the_256_row_tile_d128(oracle, S):
+    # the head-dim-128 forward works on 256-query tiles and 128-key stages: lengths on and next to
+    # their multiples, so that waves with no unmasked tile, one, and several all occur
+    case(oracle, 1, S, 1, 1, 128, seed=100 + S)
+
+
+@pytest.mark.parametrize("S", [512, 640])
+def test_non_causal_whole_tiles_d128(oracle, S):
+    # every key tile is complete and unmasked for every wave: the hand-sequenced path alone
+    case(oracle, 1, S, 2, 1, 128, causal=False, seed=110 + S)
+
+
+def test_packed_lengths_around_tiles(oracle):
+    lens = [256, 255, 257, 512, 1, 384, 129]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    case(oracle, 1, int(cu[-1]), 2, 2, 128, cu=cu, seed=121)
+
+
+def test_late_outlier_keys_move_the_reference(oracle):
+    # Two keys far into the sequence, the second larger than the first, carry scores far above
+    # everything before them for the rows that point their way: the softmax reference of those
+    # rows has to move in the middle of the unmasked tiles, twice.  Magnitudes grow with the
+    # outliers (dq and dk carry k and q), hence the wider absolute bar; the relative bar stands.
+    B, S, H, D = 1, 1300, 2, 128
+    q = randn_bf16((B, S, H, D), 131)
+    k = randn_bf16((B, S, H, D), 132).float()
+    k[:, 700] *= 12.0
+    k[:, 1000] *= 30.0
+    k = k.to(q.dtype)
+    v = randn_bf16((B, S, H, D), 133)
+    do = randn_bf16((B, S, H, D), 134)
+    scale = D ** -0.5
+    got = run_gpu(q, k, v, do, scale, True, None)
+    ref = oracle.attn_fwd_bwd(to64(q), to64(k), to64(v), to64(do), scale, True, None)
+    compare_all(got, ref, "late outliers", grad_abs_tol=30 * 5e-2)
+
+
+def test_backward_is_bitwise_reproducible_and_phases_compose():
+    import torch
+    from paper_2401_09149_amd import binding
+    B, S, Hq, Hkv, D = 2, 900, 4, 2, 128
+    dev = "cuda:0"
+    q, do = (randn_bf16((B, S, Hq, D), 141 + i).to(dev) for i in range(2))
+    k, v = (randn_bf16((B, S, Hkv, D), 143 + i).to(dev) for i in range(2))
+    scale = D ** -0.5
+    o, lse = binding.attn_fwd(q, k, v, scale, True, None)
+    o2, lse2 = binding.attn_fwd(q, k, v, scale, True, None)
+    assert torch.equal(o, o2) and torch.equal(lse, lse2)
+    first = binding.attn_bwd(q, k, v, o, do, lse, scale, True, None)
+    again = binding.attn_bwd(q, k, v, o, do, lse, scale, True, None)
+    for a, b in zip(first, again):
+        assert torch.equal(a, b)
+    # the three phases one call at a time, sharing the workspace, give the same bits
+    dq, dk, dv = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+    ws = binding.alloc_bwd_workspace(q, k, None)
+    for phase in (binding.BWD_DELTA, binding.BWD_DQ, binding.BWD_DKDV):
+        binding.ie_attn_bwd_phases(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws, phase)
+    torch.cuda.synchronize()
+    for a, b in zip(first, (dq, dk, dv)):
+        assert torch.equal(a, b)
+    for bad in (0, 8, 15):
+        with pytest.raises(binding.IeAttnError) as e:
+            binding.ie_attn_bwd_phases(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws, bad)
+        assert e.value.code == -3
+
+
 def test_error_codes_on_device_tensors():
     import torch
     from paper_2401_09149_amd import binding
