@@ -1,5 +1,6 @@
 """Builds libie_attn.so (the C-ABI library) for gfx950 with hipcc, in-tree."""
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -14,16 +15,36 @@ SOURCES = ["ie_attn_api.hip", "attn_fwd.hip", "attn_fwd_wide.hip", "attn_bwd.hip
 # meet finite references), and without it every max is preceded by a canonicalising self-max.
 # Packed fp32 VALU forms are switched off for all device code (known to misbehave on the test machines).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-fno-honor-nans", "-Wall", "-Wno-unused-command-line-argument"]
+         "-packed-fp32-ops", "-fno-honor-nans", "-Wall", "-Wno-unused-command-line-argument",
+         "-Rpass-analysis=kernel-resource-usage"]
+# Kernels that load operands into AGPRs from assembly (the compiler does not know these are
+# loads, so a spill of such a register right after the statement would save it before the data
+# has arrived) and keep ~450 registers live: they must compile without scratch.
+NO_SCRATCH = ("attn_fwd_wide_kernel", "attn_bwd_dkdv_kernelILi128E")
+
+
+def _check_scratch(src, remarks):
+    name = None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif "ScratchSize [bytes/lane]:" in line and name:
+            size = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if size and any(k in name for k in NO_SCRATCH):
+                raise RuntimeError(f"{src}: {name} spills to scratch ({size} bytes/lane); see NO_SCRATCH in build.py")
 
 
 def _compile(src, extra):
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
     cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    lines = [l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l]
+    remarks = "\n".join(l for l in lines if "remark:" in l)
+    context = re.compile(r"^\s*\d*\s*\|")   # source excerpts under a diagnostic
+    err = "\n".join(l for l in lines if "remark:" not in l and not context.match(l))
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{err}")
+    _check_scratch(src, remarks)
     return obj, err
 
 
