@@ -1,0 +1,89 @@
+"""Times the attention kernels over the per-GPU shapes of the paper's own parallel plans.
+
+The paper's computation profiler measures `self-atten(b, S, H, D/s_sp)` on a single GPU for the
+shapes its planner considers (Sec. 4.2 "Computation Profiler"); this is that sweep for the plans
+the paper lists as its own choice ("Our Work" rows of Appendix Tables 4-7): micro-batch b, all S
+tokens, heads/s_sp heads of dimension 128 (Table 1: 32, 40, 48 and 64 heads).  Inputs are N(0,1)
+rounded to bf16, drawn on the device (timing only; parity is the tests' business).
+
+    python -m paper_2401_09149_amd.self_atten_sweep [--iters 5] [--out profiles/self_atten_sweep.md]
+"""
+import argparse
+import sys
+
+# model -> (heads, {sequence length: (micro-batch b, s_sp)}), "Our Work" rows of Appendix Tables 4-7
+PLANS = {
+    "7B": (32, {4096: (2, 1), 8192: (1, 1), 16384: (1, 2), 32768: (1, 4), 65536: (1, 8), 131072: (1, 16), 262144: (1, 32)}),
+    "13B": (40, {4096: (1, 1), 8192: (8, 8), 16384: (1, 4), 32768: (1, 8), 65536: (1, 8), 131072: (1, 4), 262144: (1, 8)}),
+    "30B": (48, {4096: (1, 2), 8192: (1, 4), 16384: (1, 8), 32768: (1, 8), 65536: (1, 16), 131072: (1, 8), 262144: (1, 8)}),
+    "65B": (64, {4096: (1, 2), 8192: (1, 8), 16384: (1, 2), 32768: (1, 4), 65536: (1, 8), 131072: (1, 8), 262144: (1, 8)}),
+}
+HEAD_DIM = 128
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def shapes():
+    for model, (heads, plans) in PLANS.items():
+        for S, (b, s_sp) in plans.items():
+            assert heads % s_sp == 0
+            yield model, S, b, s_sp, heads // s_sp
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--iters", type=int, default=5)
+    ap.add_argument("--out", default=None, help="also write the table (markdown) to this file")
+    args = ap.parse_args()
+    import torch
+    from . import binding
+    if not torch.cuda.is_available():
+        print("self_atten_sweep: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    binding.load()
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    D = HEAD_DIM
+    scale = D ** -0.5
+    lines = ["| model | S | b | s_sp | heads/GPU | fwd ms | fwd TFLOP/s | bwd ms | bwd TFLOP/s | fwd+bwd % of 2.5 PFLOP/s |",
+             "|---|---|---|---|---|---|---|---|---|---|"]
+    for model, S, b, s_sp, H in shapes():
+        mk = lambda: torch.randn((b, S, H, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        q, k, v, do = mk(), mk(), mk(), mk()
+        o = torch.empty_like(q)
+        lse = torch.empty((b, H, S), dtype=torch.float32, device=dev)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws = binding.alloc_bwd_workspace(q, k, None)
+        fwd = lambda: binding.ie_attn_fwd(q, k, v, o, lse, None, scale, True)
+        bwd = lambda: binding.ie_attn_bwd_phases(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws, binding.BWD_ALL)
+
+        def timed(fn):
+            for _ in range(2):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.iters
+
+        f_ms, b_ms = timed(fwd), timed(bwd)
+        flop_f = 2.0 * b * H * float(S) ** 2 * D   # 4 S^2 D H / 2 (causal halving); backward = 2.5x
+        tf_f, tf_b = flop_f / f_ms / 1e9, 2.5 * flop_f / b_ms / 1e9
+        both = 3.5 * flop_f / (f_ms + b_ms) / 1e9
+        line = (f"| {model} | {S} | {b} | {s_sp} | {H} | {f_ms:.3f} | {tf_f:.0f} | {b_ms:.3f} | {tf_b:.0f} | "
+                f"{100 * both / PEAK_BF16_TFLOPS:.1f} |")
+        print(line, flush=True)
+        lines.append(line)
+        del q, k, v, do, o, lse, dq, dk, dv, ws
+    if args.out:
+        with open(args.out, "w") as f:
+            f.write("# self-atten(b, S, H, D/s_sp) on one MI355X over the paper's own plans (Appendix Tables 4-7, \"Our Work\")\n\n")
+            f.write(f"command: `python -m paper_2401_09149_amd.self_atten_sweep --iters {args.iters} --out <this file>`\n\n")
+            f.write("causal, head dimension 128, bf16; FLOP convention: forward 4·S²·D·H/2, backward 2.5×\n\n")
+            f.write("\n".join(lines) + "\n")
+
+
+if __name__ == "__main__":
+    main()

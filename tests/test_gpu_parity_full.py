@@ -109,6 +109,18 @@ def test_config1_s32k_h32(oracle):
     check_identities(cfg, cu, gpu_in, gpu_out)
 
 
+def test_plan_shape_13b_s16k_b1_h10(oracle):
+    # one of the shapes of the paper's own plans (13B at 16K, s_sp = 4: 10 heads per GPU) that the
+    # profiler sweep times: a head count that is not a multiple of 8 (the other workgroup order)
+    from paper_2401_09149_amd import workloads as W
+    cfg = W.AttnConfig("13b_s16k_h10_d128", 13, B=1, S=16384, Hq=10, Hkv=10, D=128)
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    S = cfg.S
+    check_rows(oracle, cfg, cu, cpu_in, gpu_out, 9, [(0, 20), (8185, 8200), (S - 20, S)])
+    check_cols(oracle, cfg, cu, cpu_in, gpu_out, 4, [(S - 140, S - 110), (12280, 12300)])
+    check_identities(cfg, cu, gpu_in, gpu_out)
+
+
 def test_config2_s128k_h8(oracle):
     from paper_2401_09149_amd import workloads as W
     cfg = W.CONFIGS[2]
