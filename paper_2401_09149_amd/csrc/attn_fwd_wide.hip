@@ -348,10 +348,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
     mfma_result_fence();
   };
 
-  // ---- masked tiles: compiler-scheduled, block by block and column block by column block
-  auto generic_block = [&](const bf16x8 (&kfr)[NKS], const bf16x8 (&vtf)[2][NDB], const bf16x8 (&qx)[NKS], f32x16 (&o_x)[NDB],
-                           ColState& st, const int lim) __attribute__((always_inline)) {
-    f32x16 s = mfma_chain_b_in_agpr<NKS>(kfr, qx);
+  // ---- masked tiles: compiler-scheduled.  Per 32-key block both score chains first, then both
+  // masks and maxima (with the rare rescale), then the exponentials and the two PV products in
+  // one region, so that the compiler can run one column block's MFMAs under the other's
+  // exponentials; the next block's fragments are requested before the current block is worked on.
+  auto masked_max = [&](f32x16& s, const int lim, ColState& st, f32x16 (&o_x)[NDB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       if (8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
@@ -360,7 +361,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
     mx = halfwave_max(mx);
     if (__builtin_amdgcn_ballot_w64(mx > st.thr) != 0) rescale(st, o_x, mx);
-    bf16x8 pf[2];
+  };
+  auto exps = [&](const f32x16& s, ColState& st, bf16x8 (&pf)[2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int sblk = 0; sblk < 2; ++sblk) {
       bf16x2 pp[4];
@@ -373,6 +375,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
       }
       pf[sblk] = cat_pairs(pp[0], pp[1], pp[2], pp[3]);
     }
+  };
+  auto pv = [&](f32x16 (&o_x)[NDB], const bf16x8 (&vtf)[2][NDB], const bf16x8 (&pf)[2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
@@ -381,14 +385,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   auto generic_tile = [&](const int T) __attribute__((always_inline)) {
     const int so = (T & 1) * TILE_BYTES;
     const int kb = T * BN;
-#pragma unroll 1
-    for (int r = 0; r < NB; ++r) {
-      const int key0 = kb + 32 * r;  // first key of the block, relative to k_begin
-      // a block is skipped when no row of the wave can see any of its keys
-      if (key0 >= nk || (p.causal && key0 > wave_row_min + 63)) break;
-      bf16x8 kfr[NKS], vtf[2][NDB];
+    bf16x8 kfr[NKS], vtf[2][NDB];
+    auto load_k = [&](const int r) __attribute__((always_inline)) {
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) kfr[ks] = lds_read8(kp[ks], so + 32 * r * ROW_BYTES);
+    };
+    auto load_v = [&](const int r) __attribute__((always_inline)) {
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
@@ -396,11 +398,36 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
           const int off = so + (32 * r + 16 * sblk) * ROW_BYTES;
           vtf[sblk][db] = cat4(lds_read_tr4(vp0[db] + off), lds_read_tr4(vp8[db] + off));
         }
+    };
+    // a block is worked on when some row of the wave can see some of its keys
+    auto visible = [&](const int r) __attribute__((always_inline)) {
+      const int key0 = kb + 32 * r;
+      return r < NB && key0 < nk && !(p.causal && key0 > wave_row_min + 63);
+    };
+    if (visible(0)) { load_k(0); load_v(0); }
+#pragma unroll 1
+    for (int r = 0; r < NB; ++r) {
+      if (!visible(r)) break;
+      const bool more = visible(r + 1);
+      const int key0 = kb + 32 * r;  // first key of the block, relative to k_begin
       // last visible key relative to the lane's first key of the block (keys 4h.. of each 8)
       const int lim_a = (p.causal ? rel_a : nk - 1) - key0 - 4 * h;
       const int lim_b = (p.causal ? rel_b : nk - 1) - key0 - 4 * h;
-      if (!(p.causal && key0 > wave_row_min + 31)) generic_block(kfr, vtf, qa, oa, sa, lim_a);
-      generic_block(kfr, vtf, qb, ob, sb, lim_b);
+      const bool do_a = !(p.causal && key0 > wave_row_min + 31);  // column a's rows end 32 earlier
+      bf16x8 pf_a[2], pf_b[2];
+      f32x16 ss_a, ss_b;
+      if (do_a) ss_a = mfma_chain_b_in_agpr<NKS>(kfr, qa);
+      ss_b = mfma_chain_b_in_agpr<NKS>(kfr, qb);
+      if (more) load_k(r + 1);  // the K fragments are free again: the next block's, a block ahead of their use
+      if (do_a) masked_max(ss_a, lim_a, sa, oa);
+      masked_max(ss_b, lim_b, sb, ob);
+      if (do_a) {
+        exps(ss_a, sa, pf_a);
+        pv(oa, vtf, pf_a);
+      }
+      exps(ss_b, sb, pf_b);
+      pv(ob, vtf, pf_b);
+      if (more) load_v(r + 1);
     }
   };
 
