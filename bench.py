@@ -31,8 +31,22 @@ def event_ms(fn, iters):
         fn()
         stop[i].record()
     torch.cuda.synchronize()
-    ts = [a.elapsed_time(b) for a, b in zip(start, stop)]
-    return sum(ts) / len(ts), min(ts)
+    ts = sorted(a.elapsed_time(b) for a, b in zip(start, stop))
+    return sum(ts) / len(ts), ts[0], ts[len(ts) // 2]
+
+
+def tile_efficiency(cfg, cu_np, bq=256, bk=128):
+    """Credited (query, key) pairs (L^2/2 per document) over the pairs the forward's tiles cover:
+    every launched (bq-query tile, bk-key tile) counted in full, masked part included."""
+    import numpy as np
+    lens = [cfg.S] if cu_np is None else [int(x) for x in np.diff(cu_np)]
+    credited = executed = 0.0
+    for L in lens:
+        credited += L * L / 2.0 if cfg.causal else float(L) * L
+        for t in range((L + bq - 1) // bq):
+            nk = min(bq * (t + 1), L) if cfg.causal else L
+            executed += float(bq) * bk * ((nk + bk - 1) // bk)
+    return credited / executed if executed else None
 
 
 def measured_traffic(workload, kernel):
@@ -134,11 +148,11 @@ def main():
 
     # Per-kernel durations, events on the launch stream (torch's current stream).
     it = max(3, min(args.steps, 10))
-    fwd_ms, fwd_min = event_ms(fwd, it)
-    bwd_ms, bwd_min = event_ms(bwd, it)
-    delta_ms, _ = event_ms(lambda: bwd(binding.BWD_DELTA), it)
-    dq_ms, _ = event_ms(lambda: bwd(binding.BWD_DQ), it)
-    dkdv_ms, _ = event_ms(lambda: bwd(binding.BWD_DKDV), it)
+    fwd_ms, fwd_min, fwd_med = event_ms(fwd, it)
+    bwd_ms, bwd_min, bwd_med = event_ms(bwd, it)
+    delta_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DELTA), it)
+    dq_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DQ), it)
+    dkdv_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DKDV), it)
 
     f_fwd = W.fwd_flops(cfg, cu_np)
     f_bwd = W.bwd_flops(cfg, cu_np)
@@ -178,10 +192,11 @@ def main():
         "config": {"workload": cfg.name, "B": cfg.B, "S": cfg.S, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D,
                    "causal": cfg.causal, "packed_docs": None if cu_np is None else len(cu_np) - 1, "seed": cfg.seed},
         "frac_of_peak": value / PEAK_BF16_TFLOPS,
-        "fwd": {"ms": fwd_ms, "ms_min": fwd_min, "tflops": fwd_tflops, "frac_of_peak": fwd_tflops / PEAK_BF16_TFLOPS},
-        "bwd": {"ms": bwd_ms, "ms_min": bwd_min, "tflops": bwd_tflops, "frac_of_peak": bwd_tflops / PEAK_BF16_TFLOPS,
+        "fwd": {"ms": fwd_ms, "ms_min": fwd_min, "ms_median": fwd_med, "tflops": fwd_tflops, "frac_of_peak": fwd_tflops / PEAK_BF16_TFLOPS},
+        "bwd": {"ms": bwd_ms, "ms_min": bwd_min, "ms_median": bwd_med, "tflops": bwd_tflops, "frac_of_peak": bwd_tflops / PEAK_BF16_TFLOPS,
                 "delta_ms": delta_ms, "dq_ms": dq_ms, "dkdv_ms": dkdv_ms},
         "peak_tflops": PEAK_BF16_TFLOPS,
+        "fwd_tile_efficiency": tile_efficiency(cfg, cu_np) if cfg.D == 128 else tile_efficiency(cfg, cu_np, 128, 64),
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

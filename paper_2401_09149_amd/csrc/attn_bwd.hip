@@ -215,18 +215,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   }
   for (; kt < nkt; ++kt) tile_step(kt, (kt & 1) * STAGE_BYTES, std::false_type{});
 
-  if (row_ok) {
-    __bf16* drow = p.dq + qhead + row * q_stride;
+  __bf16* drow = p.dq + qhead + row * q_stride;
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 w;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) w[t] = (__bf16)(acc[db][4 * q4 + t] * p.scale);
-        *reinterpret_cast<bf16x4*>(drow + 32 * db + 8 * q4 + 4 * h) = w;
-      }
-  }
+  for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc[db], p.scale, h, row_ok);
 }
 
 // ---- dK, dV ------------------------------------------------------------------------------
@@ -682,22 +673,13 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   }
 #endif
 
-  if (key_ok) {
-    __bf16* dkrow = p.dk + kvhead + key * kv_stride;
-    __bf16* dvrow = p.dv + kvhead + key * kv_stride;
+  const int64_t key_st = key_ok ? key : tc.doc_end - 1;  // (address only formed for rows that exist)
+  __bf16* dkrow = p.dk + kvhead + key_st * kv_stride;
+  __bf16* dvrow = p.dv + kvhead + key_st * kv_stride;
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 wk, wv4;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          wk[t] = (__bf16)(dkacc[db][4 * q4 + t] * p.scale);
-          wv4[t] = (__bf16)dvacc[db][4 * q4 + t];
-        }
-        *reinterpret_cast<bf16x4*>(dkrow + 32 * db + 8 * q4 + 4 * h) = wk;
-        *reinterpret_cast<bf16x4*>(dvrow + 32 * db + 8 * q4 + 4 * h) = wv4;
-      }
+  for (int db = 0; db < NDB; ++db) {
+    store_block32_bf16(dkrow + 32 * db, dkacc[db], p.scale, h, key_ok);
+    store_block32_bf16(dvrow + 32 * db, dvacc[db], 1.0f, h, key_ok);
   }
 }
 

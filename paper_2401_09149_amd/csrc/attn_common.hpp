@@ -134,6 +134,40 @@ __device__ __forceinline__ float halfwave_sum(float x) {
   return r0 + r1;
 }
 
+// Writes one lane's share of a 32-row block of a C-layout accumulator column (16 values: register
+// 4 q + t is row 8 q + 4 h + t of the block) as bf16 to the 32 contiguous elements `dst`, scaled by
+// `mul`, if `ok`.  The two half-waves first exchange quads, so that lane (n, h) holds rows 16 g + 8 h .. +7
+// (g = 0, 1) and writes two 16-byte pieces: with 8-byte pieces at a row pitch of kilobytes L2 does
+// not always merge the partial sectors before they are evicted.
+__device__ __forceinline__ void store_block32_bf16(__bf16* dst, const f32x16& acc, float mul, int h, bool ok) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  uint32_t w[4][2];  // [q][half of the quad] as packed bf16 pairs
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      bf16x2_t pr;
+      pr[0] = (__bf16)(acc[4 * q + 2 * j] * mul);
+      pr[1] = (__bf16)(acc[4 * q + 2 * j + 1] * mul);
+      w[q][j] = __builtin_bit_cast(uint32_t, pr);
+    }
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    uint32_t lo[2], hi[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      // r[0] = {a[0..31], b[0..31]}, r[1] = {a[32..63], b[32..63]} with a = quad 2g, b = quad 2g+1:
+      // lanes h = 0 get rows 16g+0..3 (own) and 16g+4..7 (partner's quad 2g);
+      // lanes h = 1 get rows 16g+8..11 (partner's quad 2g+1) and 16g+12..15 (own)
+      auto r = __builtin_amdgcn_permlane32_swap(w[2 * g][j], w[2 * g + 1][j], false, false);
+      lo[j] = r[0];
+      hi[j] = r[1];
+    }
+    u32x4 out = {lo[0], lo[1], hi[0], hi[1]};
+    if (ok) *reinterpret_cast<u32x4*>(dst + 16 * g + 8 * h) = out;  // (every lane takes part in the exchange)
+  }
+}
+
 // ---- LDS tile layout -------------------------------------------------------------------
 // A tile is ROWS x D bf16, row pitch D*2 bytes, no padding.  The 16-byte chunk c of row r
 // sits at chunk position c ^ swz(r), which keeps both access patterns spread over the

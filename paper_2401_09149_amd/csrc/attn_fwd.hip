@@ -225,29 +225,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
   // Epilogue: normalise, write O (bf16) and LSE (natural log).
   const float l_full = halfwave_sum(l);
   const float inv_l = 1.0f / l_full;
-  if (row_ok) {
-    __bf16* orow = p.o_out + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D + row * q_stride;
+  __bf16* orow = p.o_out + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D + row * q_stride;
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 w;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) w[t] = (__bf16)(oacc[db][4 * q4 + t] * inv_l);
-        *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * q4 + 4 * h) = w;
-      }
-#ifndef IE_EXP_TIMING
-    if (h == 0) p.lse_out[((int64_t)tc.b * p.Hq + tc.h) * p.S + row] = (m * c + __builtin_amdgcn_logf(l_full)) * kLn2;
-#endif
-  }
-#ifdef IE_EXP_TIMING
-  if (tid == 0) {  // timing build: the lse buffer carries (shader cycles, 100 MHz ticks, key tiles) per workgroup instead
-    unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.lse_out) + (size_t)blockIdx.x * 4;
-    dbg[0] = __builtin_readcyclecounter() - t_begin;
-    dbg[1] = wall_clock64() - w_begin;
-    dbg[2] = nkt;
-  }
-#endif
+  for (int db = 0; db < NDB; ++db) store_block32_bf16(orow + 32 * db, oacc[db], inv_l, h, row_ok);
+  if (row_ok && h == 0) p.lse_out[((int64_t)tc.b * p.Hq + tc.h) * p.S + row] = (m * c + __builtin_amdgcn_logf(l_full)) * kLn2;
 }
 
 template <int D>

@@ -511,24 +511,17 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   auto store = [&](const f32x16 (&o)[NDB], const ColState& st, const int64_t row, const bool ok) __attribute__((always_inline)) {
     const float l_full = halfwave_sum(st.l);
     const float inv_l = 1.0f / l_full;
-    if (ok) {
-      __bf16* orow = p.o_out + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D + row * q_stride;
+    __bf16* orow = p.o_out + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D + row * q_stride;
 #pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          bf16x4 w;
-#pragma unroll
-          for (int t = 0; t < 4; ++t) w[t] = (__bf16)(o[db][4 * q4 + t] * inv_l);
-          *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * q4 + 4 * h) = w;
-        }
+    for (int db = 0; db < NDB; ++db) store_block32_bf16(orow + 32 * db, o[db], inv_l, h, ok);
 #ifndef IE_EXP_TIMING
-      if (h == 0) p.lse_out[((int64_t)tc.b * p.Hq + tc.h) * p.S + row] = (st.m * c + __builtin_amdgcn_logf(l_full)) * kLn2;
+    if (ok && h == 0) p.lse_out[((int64_t)tc.b * p.Hq + tc.h) * p.S + row] = (st.m * c + __builtin_amdgcn_logf(l_full)) * kLn2;
 #endif
-    }
   };
-  store(oa, sa, row_a, ok_a);
-  store(ob, sb, row_b, ok_b);
+  // (the rows are formed again from their 32-bit positions: two 64-bit row indices kept alive
+  // through the whole kernel are four registers this kernel does not have)
+  store(oa, sa, k_begin + rel_a, ok_a);
+  store(ob, sb, k_begin + rel_b, ok_b);
 #ifdef IE_EXP_TIMING
   if (lane == 0) {  // timing build: the lse buffer carries per-wave counters instead
     unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.lse_out) + ((size_t)blockIdx.x * 4 + wv) * 8;
