@@ -34,8 +34,8 @@ def _check_scratch(src, remarks):
                 raise RuntimeError(f"{src}: {name} spills to scratch ({size} bytes/lane); see NO_SCRATCH in build.py")
 
 
-def _compile(src, extra):
-    obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+def _compile(src, extra, objdir=CSRC):
+    obj = os.path.join(objdir, src.replace(".hip", ".o"))
     cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     lines = [l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l]
@@ -46,6 +46,21 @@ def _compile(src, extra):
         raise RuntimeError(f"hipcc failed for {src}:\n{err}")
     _check_scratch(src, remarks)
     return obj, err
+
+
+def build_variant(name, extra):
+    """The library with extra compile flags (instrumented or what-if builds), as
+    _variants/libie_attn_<name>.so next to the real one; select it with IE_ATTN_LIB."""
+    vdir = os.path.join(HERE, "_variants")
+    odir = os.path.join(vdir, "obj_" + name)
+    os.makedirs(odir, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+        objs = [o for o, _ in ex.map(lambda s: _compile(s, list(extra), odir), SOURCES)]
+    lib = os.path.join(vdir, f"libie_attn_{name}.so")
+    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    return lib
 
 
 def build(verbose=False, extra=()):

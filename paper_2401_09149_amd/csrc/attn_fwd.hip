@@ -93,9 +93,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
 
   const int wave_row_min = (int)(q0 - k_begin) + wv * 32;
-#ifdef IE_EXP_TIMING
-  const unsigned long long t_begin = __builtin_readcyclecounter(), w_begin = wall_clock64();
-#endif
 
   // One 64-key LDS tile is consumed as two 32-key blocks, each with its own softmax update.
   // `stage` is the byte offset of the stage holding tile kt; FULL_NEXT says that tile kt+1
@@ -103,11 +100,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
   auto tile_step = [&](const int kt, const int stage, auto full_next) __attribute__((always_inline)) {
     const int kb = kt * BN;  // first key of the tile, relative to k_begin
     const uint32_t next_lds = lds0 + (STAGE_BYTES - stage);
-#ifdef IE_EXP_NO_GLOBAL
-    if (false) {
-#else
     if (full_next) {
-#endif
       ld.load_full(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch);
       ld.load_full(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch);
     } else if (kt + 1 < nkt) {
@@ -124,21 +117,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
       f32x16 s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#ifdef IE_EXP_PRIO
-      __builtin_amdgcn_s_setprio(IE_EXP_PRIO);
-#endif
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
-#ifdef IE_EXP_NO_LDS
-        s = mfma32(qf[(ks + 1) % NKS], qf[ks], s);
-#else
         s = mfma32(lds_read8(k_ptr[ks], stage + 32 * j * ROW_BYTES), qf[ks], s);
-#endif
       }
 
-#ifdef IE_EXP_PRIO
-      __builtin_amdgcn_s_setprio(0);
-#endif
       // V^T fragments of this block: requested now, consumed after the exponentials
       bf16x8 vfrag[2][NDB];
 #pragma unroll
@@ -146,11 +129,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const int off = stage + (32 * j + 16 * sblk) * ROW_BYTES;
-#ifdef IE_EXP_NO_LDS
-          vfrag[sblk][db] = qf[(db + sblk) % NKS];
-#else
           vfrag[sblk][db] = cat4(lds_read_tr4(v_ptr0[db] + off), lds_read_tr4(v_ptr8[db] + off));
-#endif
         }
 
       if (need_mask) {
@@ -158,14 +137,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
         for (int r = 0; r < 16; ++r)
           if (32 * j + 8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
       }
-#ifdef IE_EXP_NO_SOFTMAX
-      float mx = s[0];
-#else
       float mx = s[0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
       mx = halfwave_max(mx);
-#endif
       if (__builtin_amdgcn_ballot_w64(mx > m + slack_raw) != 0) {  // some row outgrew its reference
         const float m_new = fmaxf(m, mx);
         const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
@@ -183,28 +158,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
         bf16x2 pr[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-#ifdef IE_EXP_NO_SOFTMAX
-          const float e0 = s[8 * sblk + 2 * t], e1 = s[8 * sblk + 2 * t + 1];
-#else
           const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * sblk + 2 * t], c, -mc));
           const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * sblk + 2 * t + 1], c, -mc));
-#endif
           pr[t] = pack_bf16(e0, e1);
           l += e0 + e1;  // fp32 sum of the unrounded exponentials: lse needs more than bf16 precision
         }
         pf[sblk] = cat_pairs(pr[0], pr[1], pr[2], pr[3]);
       }
       // O^T += V^T P^T
-#ifdef IE_EXP_PRIO
-      __builtin_amdgcn_s_setprio(IE_EXP_PRIO);
-#endif
 #pragma unroll
       for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) oacc[db] = mfma32(vfrag[sblk][db], pf[sblk], oacc[db]);
-#ifdef IE_EXP_PRIO
-      __builtin_amdgcn_s_setprio(0);
-#endif
     }
     async_wait_all();  // the copies of the next stage have landed ...
     __syncthreads();   // ... for every wave, and every wave is done reading this stage

@@ -249,13 +249,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
 #pragma unroll
     for (int pos = 0; pos < 16; ++pos) {
       const int k = pos >> 1;
-#ifdef IE_EXP_W_SPREADALL
-      if (copying && (pos == 0 || pos == 8)) copy_piece(cs, 2 * copy_slot + (pos >> 3));
-#else
       // all 16 pieces in the first four phases of the round: what is issued late in the round is
       // still in flight at the barrier that ends it
       if (copying && copy_slot < 4 && (pos & 3) == 0) copy_piece(cs, 4 * copy_slot + (pos >> 2));
-#endif
       // ---- the MFMA of this slot, and the LDS read that can follow it
       if ((pos & 1) == 0) {
         if (HAS_S) {
@@ -328,11 +324,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
       // fill: K(0); S_a(0) with V^T(0); S_b(0) with the softmax of s_a(0) and K(1)
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) kf[ks] = lds_read8(kp[ks], so);
-#ifdef IE_EXP_W_SPREADALL
-      if (copying) { copy_piece(cs, 0); copy_piece(cs, 1); }  // the pieces of the phase that has no MFMAs
-#else
       if (copying) { copy_piece(cs, 0); copy_piece(cs, 1); copy_piece(cs, 2); copy_piece(cs, 3); }  // the pieces of the phase that has no MFMAs
-#endif
       asm_fence();
       phase_a(Y{}, N{}, N{}, N{}, I1{}, O0{}, I1{});
       phase_b(Y{}, N{}, Y{}, N{}, I1{}, O1{}, std::integral_constant<int, 2>{});
@@ -454,11 +446,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   // (about 16 cycles per instruction), holding back the MFMAs behind.  A delay of 20 cycles per
   // wave index after each barrier keeps them apart for the whole round.
   auto stagger = [&]() __attribute__((always_inline)) {
-#ifndef IE_EXP_W_NOSTAGGER
     if (wave_u >= 1) asm volatile("s_nop 15\n\ts_nop 3");
     if (wave_u >= 2) asm volatile("s_nop 15\n\ts_nop 3");
     if (wave_u >= 3) asm volatile("s_nop 15\n\ts_nop 3");
-#endif
   };
   agpr_loads_wait();  // Q fragments (and the first tile's copies) have arrived
   async_wait_all();
