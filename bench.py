@@ -8,7 +8,9 @@ FLOP convention: forward = 4*S^2*D*Hq / 2 (causal halving), backward = 2.5x forw
 
 Prints ONE JSON line.  `value` is fwd+bwd TFLOP/s; `roofline` describes the kernel that
 takes the most time, measured live with events on the launch stream; `cpu_baseline` times
-the fp64 oracle on the host cores on a bounded sample of the same inputs.
+the fp64 oracle on the host cores on a bounded sample of the same inputs.  After the timed
+steps, `sp_permute` reports the re-layout kernels that sit either side of attention under
+sequence parallelism (HBM-bound copies, GB/s against the HBM peak); it is not part of `value`.
 """
 import argparse
 import json
@@ -20,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz = 2516.6
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
 def event_ms(fn, iters):
@@ -85,6 +88,66 @@ def cpu_baseline(cfg, q, k, v, dout, prefix, heads):
     }
 
 
+def sp_permute_bench(cfg, iters, with_cpu, profiled_with):
+    """The eight re-layout kernels either side of the two sequence-parallel all-to-alls, on one GPU's buffers of a
+    plan of the paper; each launch reads its tensor once and writes it once (2 bytes of traffic per tensor byte).
+    Buffers rotate through a ring larger than the last-level cache, so every launch streams from and to HBM."""
+    import torch
+    from paper_2401_09149_amd import binding
+    dev = "cuda:0"
+    ring = 6
+    n, nq = cfg.n_qkv, cfg.n_o
+    nk = (n - nq) // 2
+    new = lambda m: [torch.empty(m, dtype=torch.int16, device=dev) for _ in range(ring)]
+    A, X, Q, K, V, Y = new(n), new(n), new(nq), new(nk), new(nk), new(nq)
+    for t in A + Q + K + V:
+        t.random_(-32768, 32767)
+    sq, so = (cfg.B, cfg.Sl, cfg.Hq, cfg.Hkv, cfg.D, cfg.P), (cfg.B, cfg.Sl, cfg.Hq, cfg.D, cfg.P)
+    calls = {
+        "pack_qkv": (lambda i: binding.ie_sp_pack_qkv(A[i], X[i], *sq), n),
+        "unpack_qkv": (lambda i: binding.ie_sp_unpack_qkv(A[i], Q[i], K[i], V[i], *sq), n),
+        "pack_o": (lambda i: binding.ie_sp_pack_o(Q[i], Y[i], *so), nq),
+        "unpack_o": (lambda i: binding.ie_sp_unpack_o(Q[i], Y[i], *so), nq),
+        "pack_do": (lambda i: binding.ie_sp_pack_do(Q[i], Y[i], *so), nq),
+        "unpack_do": (lambda i: binding.ie_sp_unpack_do(Q[i], Y[i], *so), nq),
+        "pack_dqkv": (lambda i: binding.ie_sp_pack_dqkv(Q[i], K[i], V[i], X[i], *sq), n),
+        "unpack_dqkv": (lambda i: binding.ie_sp_unpack_dqkv(A[i], X[i], *sq), n),
+    }
+    res, total_bytes, total_ms = {}, 0.0, 0.0
+    for name, (fn, elems) in calls.items():
+        for i in range(ring):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            fn(i % ring)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        res[name] = {"us": ms * 1e3, "GBps": 4.0 * elems / ms / 1e6}
+        total_bytes += 4.0 * elems
+        total_ms += ms
+    achieved = total_bytes / total_ms / 1e6
+    out = {"workload": cfg.name, "B": cfg.B, "Sl": cfg.Sl, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "P": cfg.P,
+           "dtype": "u16", "kernel": "sp_permute_kernel", "per_call": res,
+           "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                        "traffic": measured_traffic(profiled_with, "sp_permute_kernel"),
+                        "algorithmic_bytes": total_bytes / len(calls),
+                        "note": "all eight calls of one layer (forward and backward): bytes moved / time; traffic and "
+                                "algorithmic_bytes are means per launch over the eight calls"}}
+    if with_cpu:
+        from oracle import sp_permute as ora
+        a = A[0].cpu().numpy()
+        t0 = time.perf_counter()
+        x = ora.pack_qkv(a, *sq)
+        ora.unpack_qkv(x, *sq)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2 * 4.0 * n / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "seconds": dt,
+                               "sample": "numpy oracle, pack_qkv then unpack_qkv of the same buffer size"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +157,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-prefix", type=int, default=32768)
     ap.add_argument("--cpu-heads", type=int, default=1)
+    ap.add_argument("--sp-config", type=int, default=1, help="index into the re-layout workload table; -1 skips that part")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -202,6 +266,9 @@ def main():
     if not args.no_cpu_baseline:
         prefix = min(args.cpu_prefix, cfg.S if cu_np is None else int(cu_np[1]))
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, dout, prefix, min(args.cpu_heads, cfg.Hq))
+    if args.sp_config >= 0:
+        del q, k, v, dout, o, lse, dq, dk, dv, ws
+        out["sp_permute"] = sp_permute_bench(W.SP_CONFIGS[args.sp_config], 4 * it, not args.no_cpu_baseline, cfg.name)
     print(json.dumps(out))
 
 

@@ -57,7 +57,8 @@ typedef enum ie_attn_status {
   IE_ERR_SHAPE = -2,       /* B, S, Hq, Hkv <= 0; Hq % Hkv != 0; packed with B != 1 or num_docs < 1; size too large */
   IE_ERR_UNSUPPORTED = -3, /* D not in {64,128}; scale not finite or <= 0; causal not 0/1 */
   IE_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned (256 B) or smaller than ie_attn_bwd_workspace_bytes */
-  IE_ERR_HIP = -5          /* a HIP call failed; ie_attn_last_hip_error() has the runtime's text */
+  IE_ERR_HIP = -5,         /* a HIP call failed; ie_attn_last_hip_error() has the runtime's text */
+  IE_ERR_ALIGN = -6        /* a pointer is not 16-byte aligned (ie_sp.h) */
 } ie_attn_status;
 
 /*

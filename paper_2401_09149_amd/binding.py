@@ -1,4 +1,4 @@
-"""ctypes binding of libie_attn.so (include/ie_attn.h).  Argument marshalling only.
+"""ctypes binding of libie_attn.so (include/ie_attn.h, include/ie_sp.h).  Argument marshalling only.
 
 PyTorch supplies device memory and the current HIP stream; every step of the path runs
 in the HIP kernels behind the C ABI.  There is no fallback: if the library is missing or
@@ -13,7 +13,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("IE_ATTN_LIB") or os.path.join(_HERE, "libie_attn.so")  # override: for trying out a build
 
 EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases", "ie_attn_strerror",
-           "ie_attn_last_hip_error")
+           "ie_attn_last_hip_error",
+           "ie_sp_pack_qkv", "ie_sp_unpack_qkv", "ie_sp_pack_o", "ie_sp_unpack_o",
+           "ie_sp_pack_do", "ie_sp_unpack_do", "ie_sp_pack_dqkv", "ie_sp_unpack_dqkv")
 
 _lib = None
 
@@ -46,6 +48,13 @@ def load():
     lib.ie_attn_strerror.restype = ctypes.c_char_p
     lib.ie_attn_last_hip_error.argtypes = []
     lib.ie_attn_last_hip_error.restype = ctypes.c_char_p
+    shape_qkv, shape_o = [i64, i64, i32, i32, i32, i32, vp], [i64, i64, i32, i32, i32, vp]
+    for name, args in (("ie_sp_pack_qkv", [vp, vp] + shape_qkv), ("ie_sp_unpack_qkv", [vp] * 4 + shape_qkv),
+                       ("ie_sp_pack_o", [vp, vp] + shape_o), ("ie_sp_unpack_o", [vp, vp] + shape_o),
+                       ("ie_sp_pack_do", [vp, vp] + shape_o), ("ie_sp_unpack_do", [vp, vp] + shape_o),
+                       ("ie_sp_pack_dqkv", [vp] * 4 + shape_qkv), ("ie_sp_unpack_dqkv", [vp, vp] + shape_qkv)):
+        getattr(lib, name).argtypes = args
+        getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -151,3 +160,74 @@ def attn_bwd(q, k, v, o, dout, lse, scale, causal=True, cu_seqlens=None, workspa
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     ie_attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace)
     return dq, dk, dv
+
+
+# -- re-layouts either side of the sequence-parallel all-to-alls (include/ie_sp.h) ---------------------
+# Tensors are contiguous GPU tensors of any 2-byte dtype (bf16, or int16 bit patterns) and any shape with
+# the right number of elements; the layouts are those of the header.
+
+def _buf(t, numel, what):
+    if not t.is_cuda or t.element_size() != 2 or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous GPU tensor of a 2-byte dtype")
+    if t.numel() != numel:
+        raise ValueError(f"{what} has {t.numel()} elements, expected {numel}")
+    return t.data_ptr()
+
+
+def _sp_call(name, ptrs, shape, stream):
+    rc = getattr(load(), name)(*ptrs, *shape, _stream(stream))
+    if rc != 0:
+        _raise(rc)
+
+
+def _check_heads(Hq, Hkv, P):
+    if P < 1 or Hq % P or Hkv % P:
+        raise ValueError("the head counts must be multiples of P")
+
+
+def ie_sp_pack_qkv(qkv_local, xqkv, B, Sl, Hq, Hkv, D, P, stream=None):
+    _check_heads(Hq, Hkv, P)
+    n = B * Sl * (Hq + 2 * Hkv) * D
+    _sp_call("ie_sp_pack_qkv", (_buf(qkv_local, n, "qkv_local"), _buf(xqkv, n, "xqkv")), (B, Sl, Hq, Hkv, D, P), stream)
+
+
+def ie_sp_unpack_dqkv(xqkv, dqkv_local, B, Sl, Hq, Hkv, D, P, stream=None):
+    _check_heads(Hq, Hkv, P)
+    n = B * Sl * (Hq + 2 * Hkv) * D
+    _sp_call("ie_sp_unpack_dqkv", (_buf(xqkv, n, "xqkv"), _buf(dqkv_local, n, "dqkv_local")), (B, Sl, Hq, Hkv, D, P), stream)
+
+
+def ie_sp_unpack_qkv(xqkv, q, k, v, B, Sl, Hq, Hkv, D, P, stream=None):
+    _check_heads(Hq, Hkv, P)
+    nq, nk = B * Sl * Hq * D, B * Sl * Hkv * D
+    _sp_call("ie_sp_unpack_qkv", (_buf(xqkv, nq + 2 * nk, "xqkv"), _buf(q, nq, "q"), _buf(k, nk, "k"), _buf(v, nk, "v")),
+             (B, Sl, Hq, Hkv, D, P), stream)
+
+
+def ie_sp_pack_dqkv(dq, dk, dv, xqkv, B, Sl, Hq, Hkv, D, P, stream=None):
+    _check_heads(Hq, Hkv, P)
+    nq, nk = B * Sl * Hq * D, B * Sl * Hkv * D
+    _sp_call("ie_sp_pack_dqkv", (_buf(dq, nq, "dq"), _buf(dk, nk, "dk"), _buf(dv, nk, "dv"), _buf(xqkv, nq + 2 * nk, "xqkv")),
+             (B, Sl, Hq, Hkv, D, P), stream)
+
+
+def _sp_o(name, src, dst, B, Sl, Hq, D, P, stream):
+    _check_heads(Hq, Hq, P)
+    n = B * Sl * Hq * D
+    _sp_call(name, (_buf(src, n, "source"), _buf(dst, n, "destination")), (B, Sl, Hq, D, P), stream)
+
+
+def ie_sp_pack_o(o, xo, B, Sl, Hq, D, P, stream=None):
+    _sp_o("ie_sp_pack_o", o, xo, B, Sl, Hq, D, P, stream)
+
+
+def ie_sp_unpack_o(xo, o_local, B, Sl, Hq, D, P, stream=None):
+    _sp_o("ie_sp_unpack_o", xo, o_local, B, Sl, Hq, D, P, stream)
+
+
+def ie_sp_pack_do(dout_local, xo, B, Sl, Hq, D, P, stream=None):
+    _sp_o("ie_sp_pack_do", dout_local, xo, B, Sl, Hq, D, P, stream)
+
+
+def ie_sp_unpack_do(xo, dout, B, Sl, Hq, D, P, stream=None):
+    _sp_o("ie_sp_unpack_do", xo, dout, B, Sl, Hq, D, P, stream)

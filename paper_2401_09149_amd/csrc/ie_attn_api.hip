@@ -122,6 +122,7 @@ const char* ie_attn_strerror(int code) {
     case IE_ERR_UNSUPPORTED: return "unsupported configuration (D must be 64 or 128, scale finite and > 0, causal 0 or 1)";
     case IE_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case IE_ERR_HIP: return "a HIP runtime call failed";
+    case IE_ERR_ALIGN: return "a pointer is not 16-byte aligned";
     default: return "unknown ie_attn status";
   }
 }

@@ -11,6 +11,10 @@ import json
 import sys
 
 
+def ours(kernel):
+    return "attn_" in kernel or "sp_permute" in kernel
+
+
 def short(name):
     name = name.split("(")[0]
     return name.replace("void ", "").replace("ie::", "")
@@ -44,7 +48,7 @@ def pmc(out, command, paths):
     with open(out, "w") as f:
         f.write(f"# rocprofv3 --pmc (one run per counter group), mean per dispatch\n\ncommand: `{command}`\n\n")
         for k, cs in merged.items():
-            if not ("attn_" in k):
+            if not ours(k):
                 continue
             f.write(f"## {k}\n\n")
             for c, v in sorted(cs.items()):
@@ -58,7 +62,7 @@ def traffic(fetch_csv, write_csv, out, workload, command):
     fetch, write = per_kernel(fetch_csv), per_kernel(write_csv)
 
     def copy_value(table, counter):
-        cands = [cs[counter] for k, cs in table.items() if "attn_" not in k and counter in cs and cs[counter] > 2 ** 18]
+        cands = [cs[counter] for k, cs in table.items() if not ours(k) and counter in cs and cs[counter] > 2 ** 18]
         return max(cands) if cands else None
 
     cf, cw = copy_value(fetch, "FETCH_SIZE"), copy_value(write, "WRITE_SIZE")
@@ -68,7 +72,7 @@ def traffic(fetch_csv, write_csv, out, workload, command):
     res = {"workload": workload, "command": command, "fetch_scale": sf, "write_scale": sw,
            "copy_fetch_counter": cf, "copy_write_counter": cw, "bytes_per_launch": {}, "detail": {}}
     for k in fetch:
-        if "attn_" not in k:
+        if not ours(k):
             continue
         fb = fetch[k].get("FETCH_SIZE", 0.0) * sf * 1024.0
         wb = write.get(k, {}).get("WRITE_SIZE", 0.0) * sw * 1024.0

@@ -100,3 +100,50 @@ def fwd_flops(cfg, cu_seqlens=None):
 
 def bwd_flops(cfg, cu_seqlens=None):
     return 2.5 * fwd_flops(cfg, cu_seqlens)
+
+
+# -- the re-layouts either side of the sequence-parallel all-to-alls -----------------------------------
+
+@dataclass(frozen=True)
+class SpConfig:
+    """One GPU's buffers around the two all-to-alls of a layer (Sec. 2.2 "SP-2", Sec. 3.1): micro-batch B,
+    Sl = S/P tokens per sequence slice, Hq / Hkv heads of the whole layer, P = s_sp peers."""
+    name: str
+    index: int
+    B: int
+    Sl: int
+    Hq: int
+    Hkv: int
+    D: int
+    P: int
+
+    @property
+    def seed(self):
+        return 2000 + self.index
+
+    @property
+    def n_qkv(self):
+        return self.B * self.Sl * (self.Hq + 2 * self.Hkv) * self.D
+
+    @property
+    def n_o(self):
+        return self.B * self.Sl * self.Hq * self.D
+
+
+# The paper's own plans (Appendix Tables 4-7, "Our Work" rows) for 7B at 32K (s_sp = 4: 8 heads per GPU),
+# 7B at 256K (s_sp = 32: one head per GPU, the shortest runs) and 65B at 64K (s_sp = 8), plus a small case.
+SP_CONFIGS = [
+    SpConfig("tiny_b2_sl96_h8_kv4_d64_p4", 0, B=2, Sl=96, Hq=8, Hkv=4, D=64, P=4),
+    SpConfig("7b_s32k_sp4", 1, B=1, Sl=8192, Hq=32, Hkv=32, D=128, P=4),
+    SpConfig("7b_s256k_sp32", 2, B=1, Sl=8192, Hq=32, Hkv=32, D=128, P=32),
+    SpConfig("65b_s64k_sp8", 3, B=1, Sl=8192, Hq=64, Hkv=64, D=128, P=8),
+]
+
+
+def make_bit_patterns(n, seed, device="cpu"):
+    """n random 16-bit patterns (int16), drawn on the CPU: the permutations move bf16 values as bits, and
+    arbitrary patterns include NaNs, infinities and denormals."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    x = torch.randint(-32768, 32768, (n,), generator=gen, dtype=torch.int16)
+    return x.to(device) if device != "cpu" else x

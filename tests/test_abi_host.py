@@ -19,9 +19,12 @@ def lib():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "ie_attn.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ie_attn_\w+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(ie_(?:attn|sp)_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -38,7 +41,7 @@ def test_strerror_is_total(lib):
         s = lib.ie_attn_strerror(code)
         assert s and len(s) > 0
         seen.add(s)
-    assert len(seen) >= 7   # six statuses + "unknown"
+    assert len(seen) >= 8   # seven statuses + "unknown"
 
 
 def test_workspace_query(lib):
@@ -72,3 +75,30 @@ def test_bad_arguments_fail_before_any_launch(lib):
     assert bwd(dq=None) == -1
     assert bwd(ws=None) == -4 and bwd(ws_bytes=16) == -4 and bwd(ws=ctypes.c_void_p(264)) == -4
     assert bwd(D=32) == -3
+
+
+def test_permute_bad_arguments_fail_before_any_launch(lib):
+    one, odd = ctypes.c_void_p(256), ctypes.c_void_p(264)   # never dereferenced
+    ok = dict(B=2, Sl=128, Hq=8, Hkv=4, D=128, P=4)
+
+    def qkv(name, *ptrs, **kw):
+        a = dict(ok, **kw)
+        return getattr(lib, name)(*ptrs, a["B"], a["Sl"], a["Hq"], a["Hkv"], a["D"], a["P"], None)
+
+    def o(name, *ptrs, **kw):
+        a = dict(ok, **kw)
+        return getattr(lib, name)(*ptrs, a["B"], a["Sl"], a["Hq"], a["D"], a["P"], None)
+
+    for name, n in (("ie_sp_pack_qkv", 2), ("ie_sp_unpack_dqkv", 2), ("ie_sp_unpack_qkv", 4), ("ie_sp_pack_dqkv", 4)):
+        for bad in range(n):
+            assert qkv(name, *[None if i == bad else one for i in range(n)]) == -1
+            assert qkv(name, *[odd if i == bad else one for i in range(n)]) == -6
+        ptrs = [one] * n
+        assert qkv(name, *ptrs, Sl=0) == -2 and qkv(name, *ptrs, B=-1) == -2 and qkv(name, *ptrs, P=0) == -2
+        assert qkv(name, *ptrs, P=3) == -2 and qkv(name, *ptrs, Hkv=2) == -2     # heads not divisible by P
+        assert qkv(name, *ptrs, D=12) == -3 and qkv(name, *ptrs, D=0) == -3
+        assert qkv(name, *ptrs, Sl=2 ** 40) == -2 and qkv(name, *ptrs, B=40000) == -2
+    for name in ("ie_sp_pack_o", "ie_sp_unpack_o", "ie_sp_pack_do", "ie_sp_unpack_do"):
+        assert o(name, None, one) == -1 and o(name, one, None) == -1
+        assert o(name, odd, one) == -6 and o(name, one, odd) == -6
+        assert o(name, one, one, Sl=0) == -2 and o(name, one, one, P=3) == -2 and o(name, one, one, D=4) == -3
