@@ -21,6 +21,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-tar
 # loads, so a spill of such a register right after the statement would save it before the data
 # has arrived) and keep ~450 registers live: they must compile without scratch.
 NO_SCRATCH = ("attn_fwd_wide_kernel", "attn_bwd_dkdv_kernelILi128E")
+# Persistent kernels loop over work items around a body that leaves no register free: with machine LICM the
+# compiler hoists per-lane invariants of the item prologue out of that loop and spills to keep them.
+SOURCE_FLAGS = {"attn_fwd_wide.hip": ["-mllvm", "-disable-machine-licm"], "attn_bwd.hip": ["-mllvm", "-disable-machine-licm"]}
 
 
 def _check_scratch(src, remarks):
@@ -36,7 +39,7 @@ def _check_scratch(src, remarks):
 
 def _compile(src, extra, objdir=CSRC):
     obj = os.path.join(objdir, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *SOURCE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     lines = [l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l]
     remarks = "\n".join(l for l in lines if "remark:" in l)

@@ -17,6 +17,7 @@
 #include "attn_common.hpp"
 #include "launch.hpp"
 #include "mfma_asm.hpp"
+#include "tile_queue.hpp"
 
 namespace ie {
 
@@ -72,11 +73,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  __shared__ int s_work;
+  const uint32_t xcc = xcc_id();
+  int skip = 0;
+  for (;;) {   // persistent: one item (batch, head, query tile) per iteration (tile_queue.hpp)
+  const int item = next_work(p, &s_work, xcc, skip);
+  if (item < 0) break;
+  // (an opaque copy of the thread index: per-lane offsets are recomputed per item rather than
+  // hoisted out of this loop and kept in registers through the main loop)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
 
-  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch);
-  if (!tc.valid) return;
+  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item);
+  if (!tc.valid) continue;
   const int g = tc.h / (p.Hq / p.Hkv);
   const int64_t q0 = tc.t0;
   const int64_t q_end = (q0 + BM < tc.doc_end) ? q0 + BM : tc.doc_end;
@@ -218,6 +229,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   __bf16* drow = p.dq + qhead + row * q_stride;
 #pragma unroll
   for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc[db], p.scale, h, row_ok);
+  }  // next item
 }
 
 // ---- dK, dV ------------------------------------------------------------------------------
@@ -248,11 +260,21 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  __shared__ int s_work;
+  const uint32_t xcc = xcc_id();
+  int skip = 0;
+  for (;;) {   // persistent: one item (batch, kv head, key block) per iteration (tile_queue.hpp)
+  const int item = next_work(p, &s_work, xcc, skip);
+  if (item < 0) break;
+  // (an opaque copy of the thread index: per-lane offsets are recomputed per item rather than
+  // hoisted out of this loop and kept in registers through the main loop)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
 
-  TileCoord tc = decode_tile<BK>(p, p.Hkv, false, scratch);
-  if (!tc.valid) return;
+  TileCoord tc = decode_tile<BK>(p, p.Hkv, false, scratch, item);
+  if (!tc.valid) continue;
   const int g = tc.h;
   const int group = p.Hq / p.Hkv;
   const int64_t k0 = tc.t0;
@@ -667,7 +689,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   mfma_result_fence();  // the last assembly MFMAs have retired before the accumulators are read
 #ifdef IE_EXP_TIMING
   if (tid == 0) {
-    uint64_t* dbg = reinterpret_cast<uint64_t*>(p.dq) + (size_t)blockIdx.x * 8;
+    uint64_t* dbg = reinterpret_cast<uint64_t*>(p.dq) + (size_t)item * 8;
     dbg[0] = __builtin_readcyclecounter() - t_begin; dbg[1] = t_fast; dbg[2] = n_fast; dbg[3] = t_gen; dbg[4] = t_sync; dbg[5] = total;
     dbg[6] = t_begin; dbg[7] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));  // HW_ID
   }
@@ -681,6 +703,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     store_block32_bf16(dkrow + 32 * db, dkacc[db], p.scale, h, key_ok);
     store_block32_bf16(dvrow + 32 * db, dvacc[db], 1.0f, h, key_ok);
   }
+  }  // next item
 }
 
 template <int D>
@@ -698,10 +721,13 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     int rc = set_smem(attn_bwd_dq_kernel<D>, smem);
     if (rc) return rc;
     int64_t tiles = tiles_per_head(p.S, 128, p.cu, p.num_docs);
-    int64_t grid = tiles * p.B * p.Hq;
-    if (grid >= ((int64_t)1 << 31)) return kErrShape;
+    int64_t items = tiles * p.B * p.Hq;
+    if (items >= ((int64_t)1 << 31)) return kErrShape;
     p.tiles = (int32_t)tiles;
-    attn_bwd_dq_kernel<D><<<dim3((unsigned)grid), dim3(kThreads), smem, st>>>(p);
+    static const int per_cu = resident_per_cu(attn_bwd_dq_kernel<D>, smem);
+    const QueueLaunch ql = tile_queue_prepare(p, items, p.Hq, per_cu, st);
+    if (ql.err != hipSuccess) return hip_fail(ql.err);
+    attn_bwd_dq_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
   }
   if (phases & 4) {  // dk, dv
@@ -709,10 +735,13 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     int rc = set_smem(attn_bwd_dkdv_kernel<D>, smem);
     if (rc) return rc;
     int64_t tiles = tiles_per_head(p.S, 128, p.cu, p.num_docs);
-    int64_t grid = tiles * p.B * p.Hkv;
-    if (grid >= ((int64_t)1 << 31)) return kErrShape;
+    int64_t items = tiles * p.B * p.Hkv;
+    if (items >= ((int64_t)1 << 31)) return kErrShape;
     p.tiles = (int32_t)tiles;
-    attn_bwd_dkdv_kernel<D><<<dim3((unsigned)grid), dim3(kThreads), smem, st>>>(p);
+    static const int per_cu = resident_per_cu(attn_bwd_dkdv_kernel<D>, smem);
+    const QueueLaunch ql = tile_queue_prepare(p, items, p.Hkv, per_cu, st);
+    if (ql.err != hipSuccess) return hip_fail(ql.err);
+    attn_bwd_dkdv_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
   }
   return 0;

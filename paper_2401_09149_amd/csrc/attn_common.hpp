@@ -46,6 +46,7 @@ struct AttnParams {
   float scale, scale_log2;  // scale_log2 = scale * log2(e)
   int32_t causal;
   int32_t tiles;            // tiles per head the grid was sized for (upper bound when packed)
+  int32_t q_slot, q_per_xcd, q_total;  // persistent launches (tile_queue.hpp): counter slot, items per XCD list (0: one list), items
 };
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -373,24 +374,28 @@ struct TileCoord {
   bool valid;
 };
 
-// Tiles of `TS` tokens never straddle documents.  The hardware deals consecutive workgroups
-// round-robin to the 8 XCDs, each with its own L2.  When B*H is a multiple of 8, XCD x gets the
-// heads x, x+8, ... and walks them one after the other, all tiles of a head before the next
-// head: the workgroups that run together on an XCD then stream the SAME head's K/V (or Q/dO)
-// through its L2 nearly in lock-step, and each is fetched from HBM once per group of
-// co-resident tiles.  Otherwise heads simply alternate (head = w % (B*H)).  `heavy_last` says
-// whether high tile numbers carry the most work (forward and dq: causal rows late in a
-// document see more keys) so that the heaviest tiles of a head are dispatched first.
+// Tiles of `TS` tokens never straddle documents.  `w` is the item number a persistent workgroup
+// drew from its queue (tile_queue.hpp): item w belongs to the list of XCD w & 7 and is that
+// list's entry number w >> 3.  When B*H is a multiple of 8, list x holds the heads x, x+8, ... .
+// Its first part walks the heads one after the other, the heavier 5/8 of each head's tiles from
+// the heaviest down: the workgroups of an XCD then stream the SAME head's K/V (or Q/dO) through
+// its L2 nearly in lock-step, and each is fetched from HBM once per group of co-resident tiles.
+// Its last part holds the lighter 3/8 of the tiles of all its heads, interleaved by weight, so that
+// the items still running when the lists run empty are small (the kernel ends when the slowest
+// workgroup does).  Otherwise (B*H not a multiple of 8) there is one list and heads simply
+// alternate (head = w % (B*H)).  `heavy_last` says whether high tile numbers carry the most work
+// (forward and dq: causal rows late in a document see more keys).
 template <int TS>
-__device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads, bool heavy_last, int* scratch) {
+__device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads, bool heavy_last, int* scratch, int w) {
   TileCoord c;
   int nH = (int)p.B * heads;
-  int w = blockIdx.x;
   int hh, t;
   if (nH % 8 == 0) {
     const int xcd = w & 7, slot = w >> 3;
-    hh = xcd + 8 * (slot / p.tiles);
-    t = slot % p.tiles;
+    const int hpx = nH / 8;                        // heads per list
+    const int heavy = p.tiles - p.tiles * 3 / 8;   // tiles per head in the head-by-head part
+    if (slot < heavy * hpx) { hh = xcd + 8 * (slot / heavy); t = slot % heavy; }
+    else { const int r = slot - heavy * hpx; hh = xcd + 8 * (r % hpx); t = heavy + r / hpx; }
   } else {
     hh = w % nH;
     t = w / nH;

@@ -1,7 +1,8 @@
 // Forward kernel for head dimension 128, one wave per SIMD: O = softmax(scale * Q K^T + mask) V
 // and the per-row log-sum-exp (fused attention of Sec. 2.1 / Sec. 4.2, recast for CDNA4).
 //
-// One workgroup per (batch, head, 256-query tile); each of the 4 wavefronts owns 64 query rows
+// One item per (batch, head, 256-query tile), taken by persistent workgroups from a queue
+// (tile_queue.hpp); each of the 4 wavefronts owns 64 query rows
 // as two 32-row column blocks "a" and "b", whose Q fragments and O^T accumulators stay in
 // AGPRs for the whole kernel.  128-key K and V tiles stream through two LDS stages filled by
 // asynchronous copies.  Scores are produced transposed, S^T = K Q^T (one query column per
@@ -26,6 +27,7 @@
 #include "attn_common.hpp"
 #include "launch.hpp"
 #include "mfma_asm.hpp"
+#include "tile_queue.hpp"
 
 namespace ie {
 
@@ -57,11 +59,21 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  __shared__ int s_work;
+  const uint32_t xcc = xcc_id();
+  int skip = 0;
+  for (;;) {   // persistent: one item (batch, head, query tile) per iteration
+  const int item = next_work(p, &s_work, xcc, skip);
+  if (item < 0) break;
+  // Everything below is derived from an opaque copy of the thread index, so that the compiler
+  // recomputes the per-lane offsets for every item instead of hoisting them out of this loop and
+  // keeping them in registers through the main loop, which has none to spare.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
-
-  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch);
-  if (!tc.valid) return;
+  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item);
+  if (!tc.valid) continue;
   const int g = tc.h / (p.Hq / p.Hkv);
   const int64_t q0 = tc.t0;
   const int64_t q_end = (q0 + BM < tc.doc_end) ? q0 + BM : tc.doc_end;
@@ -524,12 +536,18 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   store(ob, sb, k_begin + rel_b, ok_b);
 #ifdef IE_EXP_TIMING
   if (lane == 0) {  // timing build: the lse buffer carries per-wave counters instead
-    unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.lse_out) + ((size_t)blockIdx.x * 4 + wv) * 8;
+    unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.lse_out) + ((size_t)item * 4 + wv) * 8;
     dbg[0] = __builtin_readcyclecounter() - t_begin;
     dbg[1] = wall_clock64() - w_begin;
-    dbg[2] = nkt; dbg[3] = n_fast; dbg[4] = t_sync; dbg[5] = t_fast;
+    dbg[2] = nkt; dbg[4] = t_sync; dbg[5] = t_fast;
+    uint32_t xcc_raw, hw;   // where the wave ran: XCD number, and the hardware id (CU, shader array, shader engine)
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)\n\ts_getreg_b32 %1, hwreg(HW_REG_HW_ID)" : "=s"(xcc_raw), "=s"(hw));
+    dbg[7] = ((unsigned long long)xcc_raw << 32) | hw;
+    dbg[3] = n_fast;
+    dbg[6] = w_begin;   // 100 MHz counter after the prologue; + dbg[1] = at exit
   }
 #endif
+  }  // next item
 }
 
 int launch_fwd_wide(AttnParams p, hipStream_t st) {
@@ -537,10 +555,12 @@ int launch_fwd_wide(AttnParams p, hipStream_t st) {
   int rc = set_smem(attn_fwd_wide_kernel, smem);
   if (rc) return rc;
   int64_t tiles = tiles_per_head(p.S, FwdWideCfg::BM, p.cu, p.num_docs);
-  int64_t grid = tiles * p.B * p.Hq;
-  if (grid >= ((int64_t)1 << 31)) return kErrShape;
+  int64_t items = tiles * p.B * p.Hq;
+  if (items >= ((int64_t)1 << 31)) return kErrShape;
   p.tiles = (int32_t)tiles;
-  attn_fwd_wide_kernel<<<dim3((unsigned)grid), dim3(kThreads), smem, st>>>(p);
+  const QueueLaunch ql = tile_queue_prepare(p, items, p.Hq, 1, st);
+  if (ql.err != hipSuccess) return hip_fail(ql.err);
+  attn_fwd_wide_kernel<<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? 0 : hip_fail(e);
 }

@@ -62,9 +62,13 @@ def measure(which):
         n = (cfg.S // 256) * cfg.Hq * 4   # waves
         d = lse.view(torch.int64).flatten()[: n * 8].cpu().numpy().reshape(n, 8).astype(float)
         cyc, wall, nkt, nfast, tsync, tfast = (d[:, i] for i in range(6))
-        print(f"forward: {ms:.3f} ms, shader clock {cyc.sum() / wall.sum() * 0.1:.3f} GHz, "
+        ghz = cyc.sum() / wall.sum() * 0.1
+        per_simd = lambda c: c.sum() / 1024 / ghz * 1e-6   # ms of one SIMD's time (one wave per SIMD, 1024 SIMDs)
+        print(f"forward: {ms:.3f} ms, shader clock {ghz:.3f} GHz, "
               f"{tfast.sum() / (nfast.sum() * 128):.1f} cycles per MFMA in the hand-sequenced tiles "
-              f"({int(nfast.sum())} of {int(nkt.sum())} wave-tiles), {tsync.sum() / nkt.sum():.0f} cycles per tile at the barrier")
+              f"({int(nfast.sum())} of {int(nkt.sum())} wave-tiles), {tsync.sum() / nkt.sum():.0f} cycles per tile at the barrier; "
+              f"per SIMD {per_simd(tfast):.3f} ms in hand-sequenced tiles, {per_simd(cyc - tfast):.3f} ms in prologue, masked tiles "
+              f"and epilogue ({(cyc - tfast).mean():.0f} cycles per workgroup), {ms - per_simd(cyc):.3f} ms idle (launch gaps, tail)")
     else:
         fwd()
         bwd(binding.BWD_DELTA)
@@ -75,7 +79,8 @@ def measure(which):
         clock = tot.sum() / 256 / (ms * 1e-3) / 1e9   # one workgroup per CU at a time, 256 CUs, all busy
         print(f"dK/dV: {ms:.3f} ms, shader clock about {clock:.2f} GHz (sum of workgroup cycles / 256 CUs / time), "
               f"{tf.sum() / nf.sum() / 128:.1f} cycles per MFMA in the hand-sequenced tiles ({int(nf.sum())} of {int(steps.sum())} steps), "
-              f"{ts.sum() / steps.sum():.0f} cycles per step at the barrier")
+              f"{ts.sum() / steps.sum():.0f} cycles per step at the barrier; per workgroup {tf.mean():.0f} cycles in hand-sequenced "
+              f"tiles, {tg.mean():.0f} in masked tiles, {(tot - tf - tg).mean():.0f} in prologue and epilogue")
 
 
 def main():
