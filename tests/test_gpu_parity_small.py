@@ -150,6 +150,62 @@ def test_backward_is_bitwise_reproducible_and_phases_compose():
         assert e.value.code == -3
 
 
+def test_overlapping_launches_on_two_streams_and_many_launches_in_a_row():
+    """The persistent kernels draw their items from per-launch counters that rotate through a fixed number
+    of slots: launches that overlap on two streams must not disturb each other, and the slots must come
+    back clean after a full rotation (more launches than slots)."""
+    import torch
+    from paper_2401_09149_amd import binding
+    dev = "cuda:0"
+    D, scale = 128, 128 ** -0.5
+    shapes = [(1, 4096, 8, 8), (2, 1500, 4, 2)]   # (B, S, Hq, Hkv): eight work lists / a single list
+    data = []
+    for i, (B, S, Hq, Hkv) in enumerate(shapes):
+        q, do = (randn_bf16((B, S, Hq, D), 151 + 10 * i + j).to(dev) for j in range(2))
+        k, v = (randn_bf16((B, S, Hkv, D), 153 + 10 * i + j).to(dev) for j in range(2))
+        o, lse = binding.attn_fwd(q, k, v, scale, True, None)
+        grads = binding.attn_bwd(q, k, v, o, do, lse, scale, True, None)
+        data.append((q, k, v, do, o, lse, grads))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    results = [[], []]
+    for rep in range(3):
+        for i, (q, k, v, do, o, lse, _) in enumerate(data):
+            with torch.cuda.stream(streams[i]):
+                o2, lse2 = binding.attn_fwd(q, k, v, scale, True, None)
+                results[i].append((o2, lse2) + tuple(binding.attn_bwd(q, k, v, o2, do, lse2, scale, True, None)))
+    torch.cuda.synchronize()
+    for i, (q, k, v, do, o, lse, grads) in enumerate(data):
+        for got in results[i]:
+            for a, b in zip(got, (o, lse) + tuple(grads)):
+                assert torch.equal(a, b)
+    q, k, v, do, o, lse, _ = data[0]
+    o3, lse3 = torch.empty_like(o), torch.empty_like(lse)
+    for _ in range(300):
+        binding.ie_attn_fwd(q, k, v, o3, lse3, None, scale, True)
+    torch.cuda.synchronize()
+    assert torch.equal(o3, o) and torch.equal(lse3, lse)
+
+
+def test_autograd_wrapper_gives_the_same_gradients():
+    import torch
+    from paper_2401_09149_amd import binding
+    from paper_2401_09149_amd.autograd import attention
+    dev = "cuda:0"
+    B, S, Hq, Hkv, D = 2, 700, 4, 2, 128
+    q, do = (randn_bf16((B, S, Hq, D), 171 + j).to(dev) for j in range(2))
+    k, v = (randn_bf16((B, S, Hkv, D), 173 + j).to(dev) for j in range(2))
+    scale = D ** -0.5
+    o_ref, lse_ref = binding.attn_fwd(q, k, v, scale, True, None)
+    ref = binding.attn_bwd(q, k, v, o_ref, do, lse_ref, scale, True, None)
+    qg, kg, vg = (t.clone().requires_grad_(True) for t in (q, k, v))
+    o = attention(qg, kg, vg)
+    assert torch.equal(o, o_ref)
+    o.backward(do)
+    for got, want in zip((qg.grad, kg.grad, vg.grad), ref):
+        assert torch.equal(got, want)
+
+
 def test_error_codes_on_device_tensors():
     import torch
     from paper_2401_09149_amd import binding
