@@ -1,4 +1,4 @@
-"""ctypes binding of libie_attn.so (include/ie_attn.h, include/ie_sp.h).  Argument marshalling only.
+"""ctypes binding of libie_attn.so (include/ie_attn.h, include/ie_sp.h, include/ie_linear.h).  Argument marshalling only.
 
 PyTorch supplies device memory and the current HIP stream; every step of the path runs
 in the HIP kernels behind the C ABI.  There is no fallback: if the library is missing or
@@ -15,7 +15,8 @@ LIB_PATH = os.environ.get("IE_ATTN_LIB") or os.path.join(_HERE, "libie_attn.so")
 EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases", "ie_attn_strerror",
            "ie_attn_last_hip_error",
            "ie_sp_pack_qkv", "ie_sp_unpack_qkv", "ie_sp_pack_o", "ie_sp_unpack_o",
-           "ie_sp_pack_do", "ie_sp_unpack_do", "ie_sp_pack_dqkv", "ie_sp_unpack_dqkv")
+           "ie_sp_pack_do", "ie_sp_unpack_do", "ie_sp_pack_dqkv", "ie_sp_unpack_dqkv",
+           "ie_linear_fwd", "ie_linear_bwd_input", "ie_linear_bwd_weight")
 
 _lib = None
 
@@ -54,6 +55,9 @@ def load():
                        ("ie_sp_pack_do", [vp, vp] + shape_o), ("ie_sp_unpack_do", [vp, vp] + shape_o),
                        ("ie_sp_pack_dqkv", [vp] * 4 + shape_qkv), ("ie_sp_unpack_dqkv", [vp, vp] + shape_qkv)):
         getattr(lib, name).argtypes = args
+        getattr(lib, name).restype = ctypes.c_int
+    for name in ("ie_linear_fwd", "ie_linear_bwd_input", "ie_linear_bwd_weight"):
+        getattr(lib, name).argtypes = [vp, vp, vp, i64, i64, i64, vp]
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -231,3 +235,35 @@ def ie_sp_pack_do(dout_local, xo, B, Sl, Hq, D, P, stream=None):
 
 def ie_sp_unpack_do(xo, dout, B, Sl, Hq, D, P, stream=None):
     _sp_o("ie_sp_unpack_do", xo, dout, B, Sl, Hq, D, P, stream)
+
+
+# -- linear modules (include/ie_linear.h) ---------------------------------------------------------------
+
+def _mat(t, rows, cols, what):
+    if not t.is_cuda or t.dtype != torch.bfloat16 or not t.is_contiguous() or tuple(t.shape) != (rows, cols):
+        raise ValueError(f"{what} must be a contiguous bf16 GPU tensor of shape ({rows}, {cols})")
+    return t.data_ptr()
+
+
+def ie_linear_fwd(x, w, y, stream=None):
+    """y[M,N] = x[M,K] w[N,K]^T"""
+    (M, K), N = x.shape, w.shape[0]
+    rc = load().ie_linear_fwd(_mat(x, M, K, "x"), _mat(w, N, K, "w"), _mat(y, M, N, "y"), M, N, K, _stream(stream))
+    if rc != 0:
+        _raise(rc)
+
+
+def ie_linear_bwd_input(dy, w, dx, stream=None):
+    """dx[M,K] = dy[M,N] w[N,K]"""
+    (M, N), K = dy.shape, w.shape[1]
+    rc = load().ie_linear_bwd_input(_mat(dy, M, N, "dy"), _mat(w, N, K, "w"), _mat(dx, M, K, "dx"), M, N, K, _stream(stream))
+    if rc != 0:
+        _raise(rc)
+
+
+def ie_linear_bwd_weight(dy, x, dw, stream=None):
+    """dw[N,K] = dy[M,N]^T x[M,K]"""
+    (M, N), K = dy.shape, x.shape[1]
+    rc = load().ie_linear_bwd_weight(_mat(dy, M, N, "dy"), _mat(x, M, K, "x"), _mat(dw, N, K, "dw"), M, N, K, _stream(stream))
+    if rc != 0:
+        _raise(rc)

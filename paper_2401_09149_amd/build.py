@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libie_attn.so")
 PEAK_PROBE = os.path.join(HERE, "mfma_peak_probe")   # standalone executable: sustained MFMA rate of the device
 ISSUE_PROBE = os.path.join(HERE, "issue_cost_probe")  # standalone executable: what fits in an MFMA's shadow
-SOURCES = ["ie_attn_api.hip", "attn_fwd.hip", "attn_fwd_wide.hip", "attn_bwd.hip", "sp_permute.hip"]
+SOURCES = ["ie_attn_api.hip", "attn_fwd.hip", "attn_fwd_wide.hip", "attn_bwd.hip", "sp_permute.hip", "linear_gemm.hip"]
 # -fno-honor-nans: the kernels never produce NaN from finite inputs (masked scores are -inf and only ever
 # meet finite references), and without it every max is preceded by a canonicalising self-max.
 # Packed fp32 VALU forms are switched off for all device code (known to misbehave on the test machines).
@@ -45,6 +45,8 @@ def _compile(src, extra, objdir=CSRC):
     remarks = "\n".join(l for l in lines if "remark:" in l)
     context = re.compile(r"^\s*\d*\s*\|")   # source excerpts under a diagnostic
     err = "\n".join(l for l in lines if "remark:" not in l and not context.match(l))
+    if r.returncode == 0 and "warning" not in err:   # only the include trail of a remark is left
+        err = ""
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{err}")
     _check_scratch(src, remarks)

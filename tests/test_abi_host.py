@@ -23,7 +23,7 @@ def declared_functions():
     for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(ie_(?:attn|sp)_\w+)\s*\(", text))
+        names |= set(re.findall(r"\b(ie_(?:attn|sp|linear)_\w+)\s*\(", text))
     return sorted(names)
 
 
@@ -102,3 +102,19 @@ def test_permute_bad_arguments_fail_before_any_launch(lib):
         assert o(name, None, one) == -1 and o(name, one, None) == -1
         assert o(name, odd, one) == -6 and o(name, one, odd) == -6
         assert o(name, one, one, Sl=0) == -2 and o(name, one, one, P=3) == -2 and o(name, one, one, D=4) == -3
+
+
+def test_linear_bad_arguments_fail_before_any_launch(lib):
+    one, odd = ctypes.c_void_p(256), ctypes.c_void_p(264)
+    i64 = ctypes.c_int64
+    for name, bad_dims in (("ie_linear_fwd", [(128, 64, 96), (128, 60, 128)]),          # K % 64, N % 8
+                           ("ie_linear_bwd_input", [(128, 96, 64), (128, 128, 60)]),    # N % 64, K % 8
+                           ("ie_linear_bwd_weight", [(96, 64, 64), (128, 60, 64), (128, 64, 60)])):
+        f = getattr(lib, name)
+        call = lambda a, b, c, M, N, K: f(a, b, c, i64(M), i64(N), i64(K), None)
+        assert call(None, one, one, 128, 128, 128) == -1 and call(one, one, None, 128, 128, 128) == -1
+        assert call(odd, one, one, 128, 128, 128) == -6 and call(one, one, odd, 128, 128, 128) == -6
+        assert call(one, one, one, 0, 128, 128) == -2 and call(one, one, one, 128, -1, 128) == -2
+        assert call(one, one, one, 128, 2 ** 22, 128) == -2
+        for dims in bad_dims:
+            assert call(one, one, one, *dims) == -3
