@@ -10,7 +10,8 @@ Prints ONE JSON line.  `value` is fwd+bwd TFLOP/s; `roofline` describes the kern
 takes the most time, measured live with events on the launch stream; `cpu_baseline` times
 the fp64 oracle on the host cores on a bounded sample of the same inputs.  After the timed
 steps, `sp_permute` reports the re-layout kernels that sit either side of attention under
-sequence parallelism (HBM-bound copies, GB/s against the HBM peak); it is not part of `value`.
+sequence parallelism (HBM-bound copies, GB/s against the HBM peak) and `linear` the linear modules of
+the same layer (MFMA-bound); neither is part of `value`.
 """
 import argparse
 import json
@@ -148,6 +149,67 @@ def sp_permute_bench(cfg, iters, with_cpu, profiled_with):
     return out
 
 
+def linear_bench(iters, with_cpu):
+    """The linear modules of one 7B layer (hidden 4096, MLP 11008; Table 1) applied to one GPU's 8192 tokens of the
+    paper's 32K plan (s_sp = 4): forward, input gradient and weight gradient of the QKV, output, gate/up and down
+    projections.  FLOP = 2 M N K per product.  torch.matmul (the vendor library) on the same operands is timed
+    beside it as context."""
+    import torch
+    from paper_2401_09149_amd import binding
+    dev = "cuda:0"
+    M = 8192
+    modules = [("qkv", 12288, 4096), ("out", 4096, 4096), ("gate_up", 22016, 4096), ("down", 4096, 11008)]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(3000)
+    mk = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    per, flop_total, ms_total, lib_ms_total = {}, 0.0, 0.0, 0.0
+    for name, N, K in modules:
+        x, w, dy = mk(M, K), mk(N, K), mk(M, N)
+        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+        ours = [timed(lambda: binding.ie_linear_fwd(x, w, y)), timed(lambda: binding.ie_linear_bwd_input(dy, w, dx)),
+                timed(lambda: binding.ie_linear_bwd_weight(dy, x, dw))]
+        lib = [timed(lambda: torch.matmul(x, w.t(), out=y)), timed(lambda: torch.matmul(dy, w, out=dx)),
+               timed(lambda: torch.matmul(dy.t(), x, out=dw))]
+        flop = 2.0 * M * N * K
+        per[name] = {"N": N, "K": K, "tflops": [flop / t / 1e9 for t in ours], "library_tflops": [flop / t / 1e9 for t in lib]}
+        flop_total += 3 * flop
+        ms_total += sum(ours)
+        lib_ms_total += sum(lib)
+        del x, w, dy, y, dx, dw
+    achieved = flop_total / ms_total / 1e9
+    out = {"workload": "7b_linear_m8192", "M": M, "dtype": "bf16", "kernel": "linear_gemm_kernel",
+           "order": ["fwd", "bwd_input", "bwd_weight"], "per_module": per, "ms_per_layer": ms_total,
+           "library_ms_per_layer": lib_ms_total,
+           "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                        "note": "all twelve products of one layer: FLOP / time"}}
+    if with_cpu:
+        import numpy as np
+        from oracle import linear as ora
+        rows, N, K = 256, 12288, 4096
+        x64 = np.random.default_rng(1).standard_normal((rows, K))
+        w64 = np.random.default_rng(2).standard_normal((N, K))
+        t0 = time.perf_counter()
+        ora.linear_fwd(x64, w64)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * rows * N * K / dt / 1e12, "unit": "TFLOP/s", "cores": os.cpu_count(), "kind": "oracle",
+                               "seconds": dt, "sample": f"fp64 oracle (numpy matmul), forward of the QKV projection on {rows} tokens"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -158,6 +220,7 @@ def main():
     ap.add_argument("--cpu-prefix", type=int, default=32768)
     ap.add_argument("--cpu-heads", type=int, default=1)
     ap.add_argument("--sp-config", type=int, default=1, help="index into the re-layout workload table; -1 skips that part")
+    ap.add_argument("--no-linear", action="store_true", help="skip the linear-module part")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -269,6 +332,10 @@ def main():
     if args.sp_config >= 0:
         del q, k, v, dout, o, lse, dq, dk, dv, ws
         out["sp_permute"] = sp_permute_bench(W.SP_CONFIGS[args.sp_config], 4 * it, not args.no_cpu_baseline, cfg.name)
+    if not args.no_linear:
+        if args.sp_config < 0:
+            del q, k, v, dout, o, lse, dq, dk, dv, ws
+        out["linear"] = linear_bench(it, not args.no_cpu_baseline)
     print(json.dumps(out))
 
 

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "attn_common.hpp"
 
 namespace ie {
@@ -16,6 +18,19 @@ int launch_fwd_wide(AttnParams p, hipStream_t st);  // head dimension 128
 int launch_bwd(AttnParams p, int D, int phases, hipStream_t st);
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Compute units of the current device (cached per device); 0 and *err set if the runtime refuses.
+inline int cu_count(hipError_t* err) {
+  static std::atomic<int> cus_of[64];
+  int dev = 0;
+  if ((*err = hipGetDevice(&dev)) != hipSuccess) return 0;
+  int cus = dev < 64 ? cus_of[dev].load(std::memory_order_relaxed) : 0;
+  if (cus == 0) {
+    if ((*err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return 0;
+    if (dev < 64) cus_of[dev].store(cus, std::memory_order_relaxed);
+  }
+  return cus;
+}
 
 // Number of `ts`-token tiles per head the grid must cover (upper bound when packed:
 // every document adds at most one partial tile).

@@ -5,8 +5,9 @@
 // ("direct": x and w in the forward, dy in dx) or with its output index contiguous ("transposed":
 // w in dx, dy and x in dw), so one kernel template with two flags serves them.
 //
-// One workgroup of 8 wavefronts (two per SIMD, so that one wave's barrier and LDS waits are
-// covered by the other's MFMAs) owns a 256 x 256 tile of C; wave (wi, wj) owns 128 x 64 of it as
+// A workgroup of 8 wavefronts (two per SIMD, so that one wave's barrier and LDS waits are
+// covered by the other's MFMAs) computes one 256 x 256 tile of C at a time (the grid is one
+// workgroup per CU, each walking its share of the tiles); wave (wi, wj) owns 128 x 64 of it as
 // 4 x 2 blocks of v_mfma_f32_32x32x16_bf16 (128 accumulator registers).  The contraction runs
 // in steps of 64 through two LDS stages of 64 KiB filled by asynchronous global->LDS copies.
 // Tiles sit in LDS in the swizzled row-major layout of attn_common.hpp; a direct operand's
@@ -14,7 +15,10 @@
 // products are formed transposed, C^T = B A^T (B's rows as the MFMA's row operand), so that a
 // lane ends up holding one row i of C with consecutive j in its registers and the epilogue
 // writes 16 bytes per lane.  Each k-step reads 4 + 2 fragments for 8 MFMAs: 0.75 KiB of LDS
-// reads per MFMA.
+// reads per MFMA, plus 0.25 KiB of copy writes: the LDS port is the busiest unit.  (Four waves
+// owning 128 x 128 each, 0.5 KiB of reads per MFMA, were tried both compiler-scheduled and with
+// a hand-written instruction order and a mid-stage barrier: with one wave per SIMD the barrier
+// and the issue cost of the copy instructions are exposed, and neither version was faster.)
 #include "../../include/ie_linear.h"
 
 #include <hip/hip_runtime.h>
@@ -25,7 +29,7 @@
 namespace ie {
 namespace {
 
-constexpr int kGemmThreads = 512;
+constexpr int kWaves = 8;
 constexpr int TI = 256, TJ = 256, TR = 64;
 constexpr int G_TILE_BYTES = TI * TR * 2;          // 32 KiB, either layout
 constexpr int G_STAGE_BYTES = 2 * G_TILE_BYTES;    // A tile | B tile
@@ -46,34 +50,34 @@ struct GemmParams {
 // (transposed) of the tile that exist along the output index; lanes past it repeat the last one.
 template <bool T>
 struct TileCopy {
-  uint32_t row;   // direct: tile row of instruction 0 (later ones add 64); transposed: r row (add 16)
-  uint32_t lc;    // logical 16-byte chunk this lane fetches
+  static constexpr int WAVES = kWaves;
+  static constexpr int NI = 32 / WAVES;   // 1 KiB instructions per wave per tile
+  uint32_t row;    // tile row this lane fetches in instruction 0: direct tiles add 8*WAVES per instruction, transposed 2*WAVES
+  uint32_t chunk;  // its 16-byte chunk POSITION inside the row
   int wave;
   __device__ __forceinline__ void init(int tid) {
     const int lane = tid & 63;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if (!T) {
-      row = 8 * wave + lane / 8;
-      lc = (lane % 8) ^ swz<64>(row);
-    } else {
-      row = 2 * wave + lane / 32;
-      lc = (lane % 32) ^ swz<256>(row);
-    }
+    row = T ? 2 * wave + lane / 32 : 8 * wave + lane / 8;
+    chunk = T ? lane % 32 : lane % 8;
   }
   // `g`: first byte of the tile in global memory (wave-uniform); `lds`: byte address of the tile.
   __device__ __forceinline__ void issue(uint32_t lds, const char* g, uint32_t pitch, int valid) const {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < NI; ++t) {
       uint32_t voff;
       if (!T) {
-        uint32_t r = row + 64 * t;
-        r = r < (uint32_t)valid ? r : (uint32_t)valid - 1;
-        voff = r * pitch + (lc << 4);
+        const uint32_t r = row + 8 * WAVES * t;
+        const uint32_t lc = chunk ^ swz<64>(r);          // the logical chunk that belongs at this position
+        const uint32_t rc = r < (uint32_t)valid ? r : (uint32_t)valid - 1;
+        voff = rc * pitch + (lc << 4);
       } else {
+        const uint32_t r = row + 2 * WAVES * t;
+        const uint32_t lc = chunk ^ swz<256>(r);
         const uint32_t ch = lc < (uint32_t)valid ? lc : (uint32_t)valid - 1;
-        voff = (row + 16 * t) * pitch + (ch << 4);
+        voff = r * pitch + (ch << 4);
       }
-      async_copy16(voff, g, lds + (uint32_t)(wave + 8 * t) * 1024);
+      async_copy16(voff, g, lds + (uint32_t)(wave + WAVES * t) * 1024);
     }
   }
 };
@@ -115,91 +119,116 @@ __device__ __forceinline__ void store_block(__bf16* dst, const f32x16& acc, int 
   }
 }
 
-// Workgroup -> tile.  The hardware deals consecutive workgroups round-robin to the 8 XCDs; XCD x
-// gets a contiguous share of the tile sequence, and the sequence walks panels of 8 i-tiles, all
-// 8 against one j-tile before the next j-tile, so that the workgroups that run together on an
-// XCD share a few A and B panels in its L2.
-__device__ __forceinline__ bool decode_gemm_tile(const GemmParams& p, int& ti, int& tj) {
+// Tile sequence.  The hardware deals consecutive workgroups round-robin to the 8 XCDs; XCD x
+// (= workgroup index % 8) works through a contiguous eighth of the sequence, and the sequence
+// walks panels of 8 i-tiles, all 8 against one j-tile before the next j-tile, so that the
+// workgroups that run together on an XCD share a few A and B panels in its L2.  `l` numbers the
+// tiles of one XCD's eighth.
+struct GemmTile {
+  const char* ga;  // first byte of the A tile of contraction step 0
+  const char* gb;
+  int64_t i0, j0;
+  int i_valid, j_valid, a_valid, b_valid;
+  bool valid;
+};
+template <bool A_T, bool B_T>
+__device__ __forceinline__ GemmTile decode_gemm_tile(const GemmParams& p, int l) {
+  GemmTile g;
   const int per = (p.tiles + 7) / 8;
-  const int t = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
-  if ((int)(blockIdx.x >> 3) >= per || t >= p.tiles) return false;
+  const int t = (int)(blockIdx.x & 7) * per + l;
+  g.valid = l < per && t < p.tiles;
+  if (!g.valid) return g;
   const int panel_tiles = kPanel * p.tiles_j;
   const int panel = t / panel_tiles, in_panel = t % panel_tiles;
   const int rows_in_panel = p.tiles_i - panel * kPanel < kPanel ? p.tiles_i - panel * kPanel : kPanel;
-  tj = in_panel / rows_in_panel;
-  ti = panel * kPanel + in_panel % rows_in_panel;
-  return true;
+  const int tj = in_panel / rows_in_panel;
+  const int ti = panel * kPanel + in_panel % rows_in_panel;
+  g.i0 = (int64_t)ti * TI;
+  g.j0 = (int64_t)tj * TJ;
+  g.i_valid = (int)(p.I - g.i0 < TI ? p.I - g.i0 : TI);
+  g.j_valid = (int)(p.J - g.j0 < TJ ? p.J - g.j0 : TJ);
+  g.ga = p.a + (A_T ? g.i0 * 2 : g.i0 * p.a_pitch);
+  g.gb = p.b + (B_T ? g.j0 * 2 : g.j0 * p.b_pitch);
+  g.a_valid = A_T ? g.i_valid / 8 : g.i_valid;
+  g.b_valid = B_T ? g.j_valid / 8 : g.j_valid;
+  return g;
 }
 
 template <bool A_T, bool B_T>
-__global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_kernel(GemmParams p) {
+__global__ __launch_bounds__(kWaves * 64, 1) void linear_gemm_kernel(GemmParams p) {
+  constexpr int NJB = 2;   // 32-column blocks per wave: it owns 128 x 64 of the tile
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
-  int ti, tj;
-  if (!decode_gemm_tile(p, ti, tj)) return;
-  const int64_t i0 = (int64_t)ti * TI, j0 = (int64_t)tj * TJ;
-  const int i_valid = (int)(p.I - i0 < TI ? p.I - i0 : TI), j_valid = (int)(p.J - j0 < TJ ? p.J - j0 : TJ);
-
-  // first byte of the tile of contraction step 0, and the advance per step
-  const char* ga = p.a + (A_T ? i0 * 2 : i0 * p.a_pitch);
-  const char* gb = p.b + (B_T ? j0 * 2 : j0 * p.b_pitch);
+  // Persistent: this workgroup takes every (gridDim/8)-th tile of its XCD's share.  The first
+  // copy of the next tile is issued in the last contraction step of the current one, so the
+  // epilogue's stores overlap it; the stage parity simply keeps running across tiles.
+  int l = (int)(blockIdx.x >> 3);
+  const int lstep = (int)(gridDim.x >> 3);
+  GemmTile cur = decode_gemm_tile<A_T, B_T>(p, l);
+  if (!cur.valid) return;
   const int64_t a_step = A_T ? TR * p.a_pitch : TR * 2;
   const int64_t b_step = B_T ? TR * p.b_pitch : TR * 2;
-  const int a_valid = A_T ? i_valid / 8 : i_valid, b_valid = B_T ? j_valid / 8 : j_valid;
 
   TileCopy<A_T> ca;
   TileCopy<B_T> cb;
   ca.init(tid);
   cb.init(tid);
   const uint32_t lds0 = lds_address(smem);
-  auto copy_stage = [&](int kt) __attribute__((always_inline)) {
-    const uint32_t base = lds0 + (kt & 1) * G_STAGE_BYTES;
-    ca.issue(base, ga + kt * a_step, (uint32_t)p.a_pitch, a_valid);
-    cb.issue(base + G_TILE_BYTES, gb + kt * b_step, (uint32_t)p.b_pitch, b_valid);
+  auto copy_stage = [&](const GemmTile& g, int kt, int stage) __attribute__((always_inline)) {
+    const uint32_t base = lds0 + stage * G_STAGE_BYTES;
+    ca.issue(base, g.ga + kt * a_step, (uint32_t)p.a_pitch, g.a_valid);
+    cb.issue(base + G_TILE_BYTES, g.gb + kt * b_step, (uint32_t)p.b_pitch, g.b_valid);
   };
 
-  const int wi = wv & 1, wj = wv >> 1;   // this wave's 128 x 64 part of the tile
-  f32x16 acc[4][2];
-#pragma unroll
-  for (int ib = 0; ib < 4; ++ib)
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[ib][jb][r] = 0.0f;
-
+  const int wi = wv & 1, wj = wv >> 1;   // this wave's part of the tile
+  f32x16 acc[4][NJB];
   const int nkt = (int)(p.R / TR);
-  copy_stage(0);
-  for (int kt = 0; kt < nkt; ++kt) {
-    async_wait_all();  // this wave's copies of stage kt have landed ...
-    __syncthreads();   // ... everyone's have, and everyone is done reading the other stage
-    if (kt + 1 < nkt) copy_stage(kt + 1);
-    const char* ta = smem + (kt & 1) * G_STAGE_BYTES;
-    const char* tb = ta + G_TILE_BYTES;
+  int stage = 0;
+  copy_stage(cur, 0, 0);
+  for (;;) {
+    l += lstep;
+    const GemmTile nxt = decode_gemm_tile<A_T, B_T>(p, l);
 #pragma unroll
-    for (int ks = 0; ks < TR / 16; ++ks) {
-      bf16x8 fi[4], fj[2];
+    for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
-      for (int ib = 0; ib < 4; ++ib) fi[ib] = frag<A_T>(ta, lane, wi * 128 + ib * 32, ks);
+      for (int jb = 0; jb < NJB; ++jb)
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb) fj[jb] = frag<B_T>(tb, lane, wj * 64 + jb * 32, ks);
+        for (int r = 0; r < 16; ++r) acc[ib][jb][r] = 0.0f;
+    for (int kt = 0; kt < nkt; ++kt) {
+      async_wait_all();  // this wave's copies of this stage have landed ...
+      __syncthreads();   // ... everyone's have, and everyone is done reading the other stage
+      if (kt + 1 < nkt) copy_stage(cur, kt + 1, stage ^ 1);
+      else if (nxt.valid) copy_stage(nxt, 0, stage ^ 1);
+      const char* ta = smem + stage * G_STAGE_BYTES;
+      const char* tb = ta + G_TILE_BYTES;
 #pragma unroll
-      for (int ib = 0; ib < 4; ++ib)
+      for (int ks = 0; ks < TR / 16; ++ks) {
+        bf16x8 fi[4], fj[NJB];
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb) acc[ib][jb] = mfma32(fj[jb], fi[ib], acc[ib][jb]);
+        for (int ib = 0; ib < 4; ++ib) fi[ib] = frag<A_T>(ta, lane, wi * 128 + ib * 32, ks);
+#pragma unroll
+        for (int jb = 0; jb < NJB; ++jb) fj[jb] = frag<B_T>(tb, lane, wj * (32 * NJB) + jb * 32, ks);
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+          for (int jb = 0; jb < NJB; ++jb) acc[ib][jb] = mfma32(fj[jb], fi[ib], acc[ib][jb]);
+      }
+      stage ^= 1;
     }
-  }
-
 #pragma unroll
-  for (int ib = 0; ib < 4; ++ib) {
-    const int il = wi * 128 + ib * 32 + n;
-    const bool ok = il < i_valid;
-    __bf16* crow = p.c + (i0 + (ok ? il : 0)) * p.c_pitch + j0;
+    for (int ib = 0; ib < 4; ++ib) {
+      const int il = wi * 128 + ib * 32 + n;
+      const bool ok = il < cur.i_valid;
+      __bf16* crow = p.c + (cur.i0 + (ok ? il : 0)) * p.c_pitch + cur.j0;
 #pragma unroll
-    for (int jb = 0; jb < 2; ++jb) {
-      const int jl = wj * 64 + jb * 32;
-      store_block(crow + jl, acc[ib][jb], h, ok, j_valid - jl);
+      for (int jb = 0; jb < NJB; ++jb) {
+        const int jl = wj * (32 * NJB) + jb * 32;
+        store_block(crow + jl, acc[ib][jb], h, ok, cur.j_valid - jl);
+      }
     }
+    if (!nxt.valid) break;
+    cur = nxt;
   }
 }
 
@@ -215,16 +244,22 @@ int check_dims(int64_t M, int64_t N, int64_t K) {
 
 template <bool A_T, bool B_T>
 int launch_gemm(GemmParams p, hipStream_t st) {
-  int rc = set_smem(linear_gemm_kernel<A_T, B_T>, G_SMEM_BYTES);
+  auto kernel = linear_gemm_kernel<A_T, B_T>;
+  int rc = set_smem(kernel, G_SMEM_BYTES);
   if (rc) return rc;
   p.tiles_i = (int)ceil_div(p.I, TI);
   p.tiles_j = (int)ceil_div(p.J, TJ);
   const int64_t tiles = (int64_t)p.tiles_i * p.tiles_j;
   if (tiles >= ((int64_t)1 << 28)) return IE_ERR_SHAPE;
   p.tiles = (int)tiles;
-  const unsigned grid = 8u * (unsigned)((p.tiles + 7) / 8);
-  linear_gemm_kernel<A_T, B_T><<<dim3(grid), dim3(kGemmThreads), G_SMEM_BYTES, st>>>(p);
-  hipError_t e = hipGetLastError();
+  hipError_t e;
+  const int cus = cu_count(&e);
+  if (e != hipSuccess) return hip_fail(e);
+  const int per = (p.tiles + 7) / 8;                      // tiles of one XCD's share
+  const int per_xcd_wgs = cus / 8 < per ? cus / 8 : per;  // one workgroup per CU (128 KiB of LDS each)
+  const unsigned grid = 8u * (unsigned)(per_xcd_wgs < 1 ? 1 : per_xcd_wgs);
+  kernel<<<dim3(grid), dim3(kWaves * 64), G_SMEM_BYTES, st>>>(p);
+  e = hipGetLastError();
   return e == hipSuccess ? IE_OK : hip_fail(e);
 }
 

@@ -20,6 +20,7 @@
 #include <atomic>
 
 #include "attn_common.hpp"
+#include "launch.hpp"
 
 namespace ie {
 
@@ -76,15 +77,9 @@ inline int resident_per_cu(K kernel, int smem_bytes) {
 struct QueueLaunch { int grid; hipError_t err; };
 inline QueueLaunch tile_queue_prepare(AttnParams& p, int64_t total, int heads, int per_cu, hipStream_t st) {
   static std::atomic<unsigned int> next_slot{0};
-  static std::atomic<int> cus_of[64];
   QueueLaunch r{0, hipSuccess};
-  int dev = 0;
-  if ((r.err = hipGetDevice(&dev)) != hipSuccess) return r;
-  int cus = dev < 64 ? cus_of[dev].load(std::memory_order_relaxed) : 0;
-  if (cus == 0) {
-    if ((r.err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return r;
-    if (dev < 64) cus_of[dev].store(cus, std::memory_order_relaxed);
-  }
+  const int cus = cu_count(&r.err);
+  if (r.err != hipSuccess) return r;
   const int64_t nH = p.B * heads;
   p.q_slot = (int32_t)(next_slot.fetch_add(1u, std::memory_order_relaxed) % kQueueSlots);
   p.q_total = (int32_t)total;

@@ -12,7 +12,7 @@ import sys
 
 
 def ours(kernel):
-    return "attn_" in kernel or "sp_permute" in kernel
+    return "attn_" in kernel or "sp_permute" in kernel or "linear_gemm" in kernel
 
 
 def short(name):
