@@ -10,12 +10,12 @@
 // workgroup per CU, each walking its share of the tiles); wave (wi, wj) owns 128 x 64 of it as
 // 4 x 2 blocks of v_mfma_f32_32x32x16_bf16 (128 accumulator registers).  The contraction runs
 // in steps of 64 through two LDS stages of 64 KiB filled by asynchronous global->LDS copies.
-// Tiles sit in LDS in the swizzled row-major layout of attn_common.hpp; a direct operand's
+// Tiles sit in LDS row-major with swizzled 16-byte chunks; a direct operand's
 // fragment is one 16-byte LDS read, a transposed operand's fragment two transpose loads.  The
 // products are formed transposed, C^T = B A^T (B's rows as the MFMA's row operand), so that a
 // lane ends up holding one row i of C with consecutive j in its registers and the epilogue
 // writes 16 bytes per lane.  Each k-step reads 4 + 2 fragments for 8 MFMAs: 0.75 KiB of LDS
-// reads per MFMA, plus 0.25 KiB of copy writes: the LDS port is the busiest unit.  (Four waves
+// reads per MFMA, plus 0.25 KiB of copy writes.  (Four waves
 // owning 128 x 128 each, 0.5 KiB of reads per MFMA, were tried both compiler-scheduled and with
 // a hand-written instruction order and a mid-stage barrier: with one wave per SIMD the barrier
 // and the issue cost of the copy instructions are exposed, and neither version was faster.)
@@ -46,6 +46,14 @@ struct GemmParams {
   int tiles_i, tiles_j, tiles;
 };
 
+// Swizzle of a direct tile (256 rows of 128 bytes): the 16-byte chunk c of row r sits at chunk position
+// c ^ dswz(r).  A 16-byte LDS read is served 16 lanes at a time across 256 bytes of banks, i.e. two rows
+// of this tile side by side, so the 16 consecutive rows of a fragment read must put the requested
+// chunk at 8 different positions for the even rows and 8 for the odd ones.  (The attention tiles'
+// swizzle, made for 256-byte rows and for transpose loads as well, gives only 4: measured, half of all
+// LDS cycles of the forward product were bank conflicts with it.)
+__device__ __forceinline__ uint32_t dswz(uint32_t r) { return (r >> 1) & 7u; }
+
 // Asynchronous copy of one operand tile into LDS.  `valid` = rows (direct) or 16-byte chunks
 // (transposed) of the tile that exist along the output index; lanes past it repeat the last one.
 template <bool T>
@@ -68,7 +76,7 @@ struct TileCopy {
       uint32_t voff;
       if (!T) {
         const uint32_t r = row + 8 * WAVES * t;
-        const uint32_t lc = chunk ^ swz<64>(r);          // the logical chunk that belongs at this position
+        const uint32_t lc = chunk ^ dswz(r);             // the logical chunk that belongs at this position
         const uint32_t rc = r < (uint32_t)valid ? r : (uint32_t)valid - 1;
         voff = rc * pitch + (lc << 4);
       } else {
@@ -86,7 +94,7 @@ struct TileCopy {
 template <bool T>
 __device__ __forceinline__ bf16x8 frag(const char* tile, int lane, int o, int ks) {
   const int n = lane & 31, h = lane >> 5;
-  if (!T) return lds_read8(tile, tile_off<64>(o + n, 2 * ks + h));
+  if (!T) return lds_read8(tile, (o + n) * 128 + (((2 * ks + h) ^ (int)dswz((uint32_t)(o + n))) << 4));
   const int c0 = o + 16 * ((lane >> 4) & 1), r0 = 16 * ks + 8 * h;
   return cat4(lds_read_tr4(tile + tr_off<256>(lane, r0, c0)), lds_read_tr4(tile + tr_off<256>(lane, r0 + 4, c0)));
 }
