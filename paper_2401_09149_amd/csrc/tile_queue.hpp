@@ -66,7 +66,7 @@ __device__ __forceinline__ int next_work(const AttnParams& p, int* s_work, uint3
 
 // Workgroups of `kernel` that fit on one CU together (registers, LDS); at least 1.
 template <typename K>
-inline int resident_per_cu(K kernel, int smem_bytes) {
+static inline int resident_per_cu(K kernel, int smem_bytes) {
   int n = 0;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(kernel), kThreads, (size_t)smem_bytes) != hipSuccess) n = 1;
   return n < 1 ? 1 : n;
@@ -74,8 +74,10 @@ inline int resident_per_cu(K kernel, int smem_bytes) {
 
 // Host side: fills the queue fields of `p` for `total` items (= tiles per head x B x heads) and
 // clears the slot on `st`.  Returns the grid size for `per_cu` resident workgroups per CU.
+// (static: every translation unit that includes this header has its own counter array and reset kernel,
+// and must call its own copy of this function; a shared inline copy would clear one unit's array for all.)
 struct QueueLaunch { int grid; hipError_t err; };
-inline QueueLaunch tile_queue_prepare(AttnParams& p, int64_t total, int heads, int per_cu, hipStream_t st) {
+static inline QueueLaunch tile_queue_prepare(AttnParams& p, int64_t total, int heads, int per_cu, hipStream_t st) {
   static std::atomic<unsigned int> next_slot{0};
   QueueLaunch r{0, hipSuccess};
   const int cus = cu_count(&r.err);

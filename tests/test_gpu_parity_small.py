@@ -179,12 +179,21 @@ def test_overlapping_launches_on_two_streams_and_many_launches_in_a_row():
         for got in results[i]:
             for a, b in zip(got, (o, lse) + tuple(grads)):
                 assert torch.equal(a, b)
-    q, k, v, do, o, lse, _ = data[0]
+    q, k, v, do, o, lse, grads = data[0]
     o3, lse3 = torch.empty_like(o), torch.empty_like(lse)
-    for _ in range(300):
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = binding.alloc_bwd_workspace(q, k, None)
+    for _ in range(300):   # forward and backward kernels keep their counters in separate arrays: rotate both
         binding.ie_attn_fwd(q, k, v, o3, lse3, None, scale, True)
+        binding.ie_attn_bwd(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws)
+    for t in (o3, lse3, dq, dk, dv):
+        t.fill_(float("nan"))
+    binding.ie_attn_fwd(q, k, v, o3, lse3, None, scale, True)
+    binding.ie_attn_bwd(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws)
     torch.cuda.synchronize()
     assert torch.equal(o3, o) and torch.equal(lse3, lse)
+    for got, want in zip((dq, dk, dv), grads):
+        assert torch.equal(got, want)
 
 
 def test_autograd_wrapper_gives_the_same_gradients():
