@@ -62,6 +62,11 @@ def traffic(fetch_csv, write_csv, out, workload, command):
     fetch, write = per_kernel(fetch_csv), per_kernel(write_csv)
 
     def copy_value(table, counter):
+        # the runtime's device-to-device copy kernel (torch's copy_ of a contiguous buffer); failing that,
+        # the largest kernel that is not one of ours
+        named = [cs[counter] for k, cs in table.items() if "copyBuffer" in k and counter in cs and cs[counter] > 2 ** 18]
+        if named:
+            return max(named)
         cands = [cs[counter] for k, cs in table.items() if not ours(k) and counter in cs and cs[counter] > 2 ** 18]
         return max(cands) if cands else None
 
