@@ -679,6 +679,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   agpr_loads_wait();  // K/V fragments (and the first stage's copies) have arrived
   async_wait_all();
   __syncthreads();
+#ifdef IE_EXP_TIMING
+  const uint64_t t_ready = __builtin_readcyclecounter();
+#endif
   int st = 0;
   for (; st + 1 < total; st += 2) {
     step_fn(st, std::integral_constant<int, 0>{});
@@ -691,7 +694,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   if (tid == 0) {
     uint64_t* dbg = reinterpret_cast<uint64_t*>(p.dq) + (size_t)item * 8;
     dbg[0] = __builtin_readcyclecounter() - t_begin; dbg[1] = t_fast; dbg[2] = n_fast; dbg[3] = t_gen; dbg[4] = t_sync; dbg[5] = total;
-    dbg[6] = t_begin; dbg[7] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));  // HW_ID
+    dbg[6] = t_ready - t_begin;   // waiting for K/V fragments and the first stage
+    dbg[7] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));  // HW_ID
   }
 #endif
 

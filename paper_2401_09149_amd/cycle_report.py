@@ -75,12 +75,13 @@ def measure(which):
         ms = timed(lambda: bwd(binding.BWD_DKDV))
         n = (cfg.S // 128) * cfg.Hkv      # workgroups
         d = dq.view(torch.int64).flatten()[: n * 8].cpu().numpy().reshape(n, 8).astype(float)
-        tot, tf, nf, tg, ts, steps = (d[:, i] for i in range(6))
+        tot, tf, nf, tg, ts, steps, tready = (d[:, i] for i in range(7))
         clock = tot.sum() / 256 / (ms * 1e-3) / 1e9   # one workgroup per CU at a time, 256 CUs, all busy
         print(f"dK/dV: {ms:.3f} ms, shader clock about {clock:.2f} GHz (sum of workgroup cycles / 256 CUs / time), "
               f"{tf.sum() / nf.sum() / 128:.1f} cycles per MFMA in the hand-sequenced tiles ({int(nf.sum())} of {int(steps.sum())} steps), "
               f"{ts.sum() / steps.sum():.0f} cycles per step at the barrier; per workgroup {tf.mean():.0f} cycles in hand-sequenced "
-              f"tiles, {tg.mean():.0f} in masked tiles, {(tot - tf - tg).mean():.0f} in prologue and epilogue")
+              f"tiles, {tg.mean():.0f} in masked tiles, {ts.mean():.0f} at barriers, {tready.mean():.0f} waiting for K/V and the first stage, "
+              f"{(tot - tf - tg - ts - tready).mean():.0f} in the rest (descriptor arithmetic between steps, flush of the last tile, the counters themselves)")
 
 
 def main():
