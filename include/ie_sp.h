@@ -34,9 +34,12 @@
  * Conventions: as in ie_attn.h (device pointers owned by the caller, work enqueued on `stream`,
  * no host synchronisation, no allocation, status codes of ie_attn_status).  Source and destination
  * must not overlap.  Every pointer must be 16-byte aligned (IE_ERR_ALIGN).  Supported: P, B, Sl,
- * Hq, Hkv >= 1 with Hq % P == 0 and Hkv % P == 0 (IE_ERR_SHAPE otherwise), D a positive multiple
- * of 8 (IE_ERR_UNSUPPORTED otherwise), every buffer below 2^40 elements.  Outputs are fully
- * overwritten.  On error nothing has been launched, except for IE_ERR_HIP.
+ * Hq, Hkv >= 1 with Hq % P == 0 and Hkv % P == 0, P * B <= 65535 and every buffer below 2^40 elements
+ * (IE_ERR_SHAPE otherwise), D a positive multiple of 8 (IE_ERR_UNSUPPORTED otherwise).  Outputs are
+ * fully overwritten.  On error nothing has been launched, except for IE_ERR_HIP.
+ * With B == 1 the layouts of o (dout) and xo coincide (the sequence slices of [1][P*Sl][Hql][D] are already
+ * contiguous chunks): ie_sp_pack_o and ie_sp_unpack_do are then plain copies, and a caller may hand o
+ * to the exchange directly and receive dout in place.
  */
 #ifndef IE_SP_H
 #define IE_SP_H
