@@ -22,7 +22,8 @@
  *
  * Common conventions
  *   - Every pointer is a DEVICE pointer on the current HIP device; the caller owns all
- *     buffers.  The library keeps no state and never synchronises with the host: all
+ *     buffers.  The library allocates nothing and never synchronises with the host (its only state is a
+ *     small device array of work-queue counters that every launch clears for itself on `stream`): all
  *     work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and the buffers must stay alive until the stream has passed it.
  *   - q, o, dout, dq : contiguous [B, S, Hq,  D] bf16.
