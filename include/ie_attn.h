@@ -26,6 +26,8 @@
  *     small device array of work-queue counters that every launch clears for itself on `stream`): all
  *     work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and the buffers must stay alive until the stream has passed it.
+ *     Calls may overlap on different streams; each launch takes the next of 256 counter slots, so
+ *     more than 256 launches of one kernel in flight at once would share one.
  *   - q, o, dout, dq : contiguous [B, S, Hq,  D] bf16.
  *     k, v, dk, dv   : contiguous [B, S, Hkv, D] bf16.
  *     lse            : contiguous [B, Hq, S] fp32, natural log, `scale` included.
