@@ -1,6 +1,7 @@
-"""torch.autograd face of the attention kernels: `attention(q, k, v, ...)` runs ie_attn_fwd and, in
-backward, ie_attn_bwd on the saved o and log-sum-exp (the probabilities are recomputed, Sec. 3.1).
-Only tensor bookkeeping happens here; there is no fallback path."""
+"""torch.autograd face of the kernels: `attention(q, k, v, ...)` runs ie_attn_fwd and, in backward, ie_attn_bwd
+on the saved o and log-sum-exp (the probabilities are recomputed, Sec. 3.1); `linear(x, w)` runs the three
+products of a Linear module without bias (Sec. 4.2).  Only tensor bookkeeping happens here; there is no
+fallback path."""
 import torch
 
 from . import binding
@@ -30,3 +31,36 @@ def attention(q, k, v, scale=None, causal=True, cu_seqlens=None, return_lse=Fals
         scale = q.shape[-1] ** -0.5
     o, lse = _Attention.apply(q, k, v, float(scale), bool(causal), cu_seqlens)
     return (o, lse) if return_lse else o
+
+
+class _Linear(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, w):
+        lead = x.shape[:-1]
+        x2 = x.reshape(-1, x.shape[-1]).contiguous()
+        w = w.contiguous()
+        y = torch.empty((x2.shape[0], w.shape[0]), dtype=torch.bfloat16, device=x.device)
+        binding.ie_linear_fwd(x2, w, y)
+        ctx.save_for_backward(x2, w)
+        ctx.lead = lead
+        return y.reshape(*lead, w.shape[0])
+
+    @staticmethod
+    def backward(ctx, dy):
+        x2, w = ctx.saved_tensors
+        dy2 = dy.reshape(-1, dy.shape[-1]).contiguous()
+        dx = dw = None
+        if ctx.needs_input_grad[0]:
+            dx = torch.empty_like(x2)
+            binding.ie_linear_bwd_input(dy2, w, dx)
+            dx = dx.reshape(*ctx.lead, x2.shape[1])
+        if ctx.needs_input_grad[1]:
+            dw = torch.empty_like(w)
+            binding.ie_linear_bwd_weight(dy2, x2, dw)
+        return dx, dw
+
+
+def linear(x, w):
+    """y = x w^T for x [..., K] and w [N, K] (bf16, on the GPU), differentiable in both.  The token count (product of
+    the leading dimensions) must be a multiple of 64 for the weight gradient, K and N multiples of 64."""
+    return _Linear.apply(x, w)

@@ -94,3 +94,39 @@ def test_paper_shapes_sampled():
     close(dx[rows], lin.linear_bwd_input(f64(dy[rows]), f64(w)), N, "dx rows")
     nrows = np.sort(rng.choice(N, 64, replace=False))
     close(dw[nrows], lin.linear_bwd_weight(f64(dy[:, nrows]), f64(x)), M, "dw rows")
+
+
+def test_autograd_layer_slice_runs_end_to_end():
+    """QKV projection -> attention -> output projection through the autograd wrappers, against torch on the same
+    bf16 operands (a composition check; each kernel has its own parity test against its oracle)."""
+    from paper_2401_09149_amd.autograd import attention, linear
+    B, S, H, heads = 1, 512, 256, 2
+    D = H // heads
+    x = randn_bf16((B, S, H), 31).to(DEV).requires_grad_(True)
+    wqkv = (randn_bf16((3 * H, H), 32) * 0.06).to(torch.bfloat16).to(DEV).requires_grad_(True)
+    wo = (randn_bf16((H, H), 33) * 0.06).to(torch.bfloat16).to(DEV).requires_grad_(True)
+    dy = randn_bf16((B, S, H), 34).to(DEV)
+
+    def layer(lin, att):
+        qkv = lin(x, wqkv).reshape(B, S, 3, heads, D)
+        o = att(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2])
+        return lin(o.reshape(B, S, H), wo)
+
+    def ref_att(q, k, v):
+        qf, kf, vf = (t.float().transpose(1, 2) for t in (q, k, v))
+        s = qf @ kf.transpose(-1, -2) * D ** -0.5
+        s = s.masked_fill(torch.triu(torch.ones(S, S, dtype=torch.bool, device=DEV), 1), float("-inf"))
+        return (torch.softmax(s, -1) @ vf).transpose(1, 2).to(torch.bfloat16)
+
+    y = layer(linear, attention)
+    y.backward(dy)
+    got = [y.detach().float()] + [t.grad.float() for t in (x, wqkv, wo)]
+    for t in (x, wqkv, wo):
+        t.grad = None
+    yr = layer(lambda a, w: (a.float() @ w.float().t()).to(torch.bfloat16), ref_att)
+    yr.backward(dy)
+    want = [yr.detach().float()] + [t.grad.float() for t in (x, wqkv, wo)]
+    for name, g, r in zip(("y", "dx", "dwqkv", "dwo"), got, want):
+        rel = (g - r).norm() / r.norm()
+        print(name, float(rel), flush=True)
+        assert rel < 2e-2, (name, float(rel))
