@@ -1,8 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the attention hot path on one MI355X.
 
-A step is one pass of the whole path (forward, then backward: delta, dQ, dK/dV) over one
-batch of seeded synthetic input that is already resident in HBM.  The workload is the
+A step is one pass of the whole path (forward, then backward: delta, dK/dV, dQ) over one
+batch of seeded synthetic input that is already resident in HBM.  The backward pass gets the
+workspace of ie_attn_bwd_fast_workspace_bytes (room for dS, B*Hq*S*(S+128) bytes more) unless
+--recompute-ds is given: with it the dK/dV kernel stores dS and dQ is one product instead of three.  The workload is the
 7B-class layer with all heads on one GPU: B=1, S=32768, Hq=Hkv=32, D=128, causal, bf16.
 FLOP convention: forward = 4*S^2*D*Hq / 2 (causal halving), backward = 2.5x forward.
 
@@ -221,6 +223,8 @@ def main():
     ap.add_argument("--cpu-heads", type=int, default=1)
     ap.add_argument("--sp-config", type=int, default=1, help="index into the re-layout workload table; -1 skips that part")
     ap.add_argument("--no-linear", action="store_true", help="skip the linear-module part")
+    ap.add_argument("--recompute-ds", action="store_true",
+                    help="give the backward pass the small workspace only: dQ recomputes S, P and dP instead of reading a stored dS")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -244,7 +248,8 @@ def main():
     o = torch.empty_like(q)
     lse = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device=dev)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    ws = binding.alloc_bwd_workspace(q, k, cu)
+    ws = binding.alloc_bwd_workspace(q, k, cu, fast=not args.recompute_ds, causal=cfg.causal)
+    stored_ds = ws.numel() > binding.ie_attn_bwd_workspace_bytes(cfg.B, cfg.S, cfg.Hq, cfg.Hkv, cfg.D, 0 if cu is None else cu.numel() - 1)
 
     def fwd():
         binding.ie_attn_fwd(q, k, v, o, lse, cu, cfg.scale, cfg.causal)
@@ -278,8 +283,8 @@ def main():
     fwd_ms, fwd_min, fwd_med = event_ms(fwd, it)
     bwd_ms, bwd_min, bwd_med = event_ms(bwd, it)
     delta_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DELTA), it)
-    dq_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DQ), it)
     dkdv_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DKDV), it)
+    dq_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DQ), it)   # (with a stored dS: reads what the dK/dV phase just left)
 
     f_fwd = W.fwd_flops(cfg, cu_np)
     f_bwd = W.bwd_flops(cfg, cu_np)
@@ -291,17 +296,27 @@ def main():
     # visible (query, key) pair and query head: forward 4D (S, PV); dK/dV kernel 8D (S, dP, dV,
     # dK); dQ kernel 6D (S, dP recomputed, dQ), of which only the dQ product (2D) is not
     # already counted in the dK/dV kernel.  Pairs are counted as L^2/2 per document.
+    # With a stored dS the dQ kernel is one product (2D) and bound by reading dS: 2 bytes per
+    # pair of the block triangle, B*Hq*S*(S+128) in all, plus K once per query tile from L2.
     pairs = f_fwd / (4.0 * cfg.D)   # = B * Hq * sum L^2 / 2
     kernels = {
         ("attn_fwd_wide_kernel" if cfg.D == 128 else "attn_fwd_kernel"): (fwd_ms, 4.0 * cfg.D * pairs),
         "attn_bwd_dkdv_kernel": (dkdv_ms, 8.0 * cfg.D * pairs),
-        "attn_bwd_dq_kernel": (dq_ms, 6.0 * cfg.D * pairs),
     }
+    if stored_ds:
+        kernels["attn_bwd_dq_from_ds_kernel"] = (dq_ms, float(cfg.B) * cfg.Hq * cfg.S * (cfg.S + 128))   # bytes
+    else:
+        kernels["attn_bwd_dq_kernel"] = (dq_ms, 6.0 * cfg.D * pairs)
     dom = max(kernels, key=lambda n: kernels[n][0])
-    dom_ms, dom_flop = kernels[dom]
-    achieved = dom_flop / (dom_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg.name, dom), "ms": dom_ms}
+    dom_ms, dom_work = kernels[dom]
+    if dom == "attn_bwd_dq_from_ds_kernel":
+        achieved = dom_work / (dom_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": measured_traffic(cfg.name, dom), "ms": dom_ms}
+    else:
+        achieved = dom_work / (dom_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg.name, dom), "ms": dom_ms}
 
     out = {
         "metric": "causal attention fwd+bwd TFLOPS and % of bf16 MFMA peak, 1 MI355X, S=32K D=128",
@@ -321,7 +336,8 @@ def main():
         "frac_of_peak": value / PEAK_BF16_TFLOPS,
         "fwd": {"ms": fwd_ms, "ms_min": fwd_min, "ms_median": fwd_med, "tflops": fwd_tflops, "frac_of_peak": fwd_tflops / PEAK_BF16_TFLOPS},
         "bwd": {"ms": bwd_ms, "ms_min": bwd_min, "ms_median": bwd_med, "tflops": bwd_tflops, "frac_of_peak": bwd_tflops / PEAK_BF16_TFLOPS,
-                "delta_ms": delta_ms, "dq_ms": dq_ms, "dkdv_ms": dkdv_ms},
+                "delta_ms": delta_ms, "dq_ms": dq_ms, "dkdv_ms": dkdv_ms,
+                "path": "stored_ds" if stored_ds else "recompute", "workspace_bytes": ws.numel()},
         "peak_tflops": PEAK_BF16_TFLOPS,
         "fwd_tile_efficiency": tile_efficiency(cfg, cu_np) if cfg.D == 128 else tile_efficiency(cfg, cu_np, 128, 64),
         "roofline": roofline,

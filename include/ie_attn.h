@@ -81,12 +81,26 @@ int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
 size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs);
 
 /*
+ * Bytes of workspace with which ie_attn_bwd trades memory for matrix work.  For dense (num_docs == 0) causal input
+ * with D == 128 and S a multiple of 128 this is ie_attn_bwd_workspace_bytes(...) plus B * Hq * S * (S + 128) bytes:
+ * room for dS = P o (dP - delta) in bf16 (the lower block triangle of every head).  Given that much, the dK/dV kernel
+ * stores the dS it forms and dQ = scale * dS K is computed from it, instead of recomputing S, P and dP a second time
+ * for dQ (seven matrix products per block pair instead of nine; Sec. 4.3 counts the backward pass as the
+ * compute-heavier direction).  The results differ from the recomputing path only in summation order (same bf16 dS,
+ * fp32 accumulation).  For every other shape the function returns ie_attn_bwd_workspace_bytes(...): there is no such
+ * path and a larger workspace changes nothing.  Pure host arithmetic.
+ */
+size_t ie_attn_bwd_fast_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs,
+                                        int32_t causal);
+
+/*
  * Backward: given dout and the forward's o and lse, writes dq, dk, dv (fully
  * overwritten; dk/dv are summed over the Hq/Hkv query heads of each kv head).  The
  * probabilities are recomputed from lse (Sec. 3.1), backward costs 2.5x the forward's
  * matrix work (cf. Sec. 4.3: backward is about twice as compute-intensive as forward).
  * `workspace` is caller-owned scratch of at least ie_attn_bwd_workspace_bytes(...) bytes,
- * 256-byte aligned; its contents after the call are unspecified.  Every output element
+ * 256-byte aligned; its contents after the call are unspecified.  With at least
+ * ie_attn_bwd_fast_workspace_bytes(...) bytes the dS-storing path described there is taken.  Every output element
  * has a single owner and a fixed summation order, so results are bitwise reproducible.
  */
 int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -101,7 +115,8 @@ int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
  * that time one kernel at a time.  `phases` is a bit mask: IE_BWD_DELTA (delta = rowsum(dO o O)
  * and lse * log2(e), both negated, into the workspace), IE_BWD_DQ (writes dq; needs what IE_BWD_DELTA left in the
  * workspace), IE_BWD_DKDV (writes dk and dv; needs the same).  Outputs of phases that are not selected are left
- * untouched.  ie_attn_bwd(...) is ie_attn_bwd_phases(..., IE_BWD_ALL).  A mask of 0 or with
+ * untouched.  On the dS-storing path (ie_attn_bwd_fast_workspace_bytes) IE_BWD_DKDV also leaves dS in the workspace
+ * and IE_BWD_DQ needs it: run IE_BWD_DKDV before IE_BWD_DQ there.  ie_attn_bwd(...) is ie_attn_bwd_phases(..., IE_BWD_ALL).  A mask of 0 or with
  * other bits set is IE_ERR_UNSUPPORTED.
  */
 enum { IE_BWD_DELTA = 1, IE_BWD_DQ = 2, IE_BWD_DKDV = 4, IE_BWD_ALL = 7 };

@@ -12,7 +12,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("IE_ATTN_LIB") or os.path.join(_HERE, "libie_attn.so")  # override: for trying out a build
 
-EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases", "ie_attn_strerror",
+EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd_fast_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases", "ie_attn_strerror",
            "ie_attn_last_hip_error",
            "ie_sp_pack_qkv", "ie_sp_unpack_qkv", "ie_sp_pack_o", "ie_sp_unpack_o",
            "ie_sp_pack_do", "ie_sp_unpack_do", "ie_sp_pack_dqkv", "ie_sp_unpack_dqkv",
@@ -41,6 +41,8 @@ def load():
     lib.ie_attn_fwd.restype = ctypes.c_int
     lib.ie_attn_bwd_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32]
     lib.ie_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.ie_attn_bwd_fast_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32, i32]
+    lib.ie_attn_bwd_fast_workspace_bytes.restype = ctypes.c_size_t
     lib.ie_attn_bwd.argtypes = [vp] * 9 + [vp, i32, i64, i64, i32, i32, i32, f32, i32, vp, ctypes.c_size_t, vp]
     lib.ie_attn_bwd.restype = ctypes.c_int
     lib.ie_attn_bwd_phases.argtypes = [vp] * 9 + [vp, i32, i64, i64, i32, i32, i32, f32, i32, vp, ctypes.c_size_t, i32, vp]
@@ -107,6 +109,10 @@ def ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs=0):
     return int(load().ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs))
 
 
+def ie_attn_bwd_fast_workspace_bytes(B, S, Hq, Hkv, D, num_docs=0, causal=True):
+    return int(load().ie_attn_bwd_fast_workspace_bytes(B, S, Hq, Hkv, D, num_docs, int(bool(causal))))
+
+
 def ie_attn_fwd(q, k, v, o, lse, cu_seqlens, scale, causal, stream=None):
     """o[B,S,Hq,D] bf16 and lse[B,Hq,S] fp32 are overwritten; all tensors live on the GPU."""
     B, S, Hq, Hkv, D = _shape(q, k)
@@ -152,10 +158,13 @@ def attn_fwd(q, k, v, scale, causal=True, cu_seqlens=None):
     return o, lse
 
 
-def alloc_bwd_workspace(q, k, cu_seqlens=None):
+def alloc_bwd_workspace(q, k, cu_seqlens=None, fast=False, causal=True):
+    """`fast`: with room for dS where the shape has that path (ie_attn_bwd_fast_workspace_bytes)."""
     B, S, Hq, Hkv, D = _shape(q, k)
     nd = 0 if cu_seqlens is None else cu_seqlens.numel() - 1
-    return torch.empty(ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, nd), dtype=torch.uint8, device=q.device)
+    size = (ie_attn_bwd_fast_workspace_bytes(B, S, Hq, Hkv, D, nd, causal) if fast
+            else ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, nd))
+    return torch.empty(size, dtype=torch.uint8, device=q.device)
 
 
 def attn_bwd(q, k, v, o, dout, lse, scale, causal=True, cu_seqlens=None, workspace=None):

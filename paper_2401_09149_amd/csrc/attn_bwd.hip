@@ -250,7 +250,7 @@ struct DkdvCfg {
   static constexpr int SMEM_BYTES = STAGES * STAGE_BYTES;
 };
 
-template <int D>
+template <int D, bool STORE_DS>
 __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p) {
   using C = DkdvCfg<D>;
   constexpr int BK = C::BK, BQ = C::BQ, NB = C::NB;
@@ -361,6 +361,15 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   const bool key_ok = key < tc.doc_end;
   const int64_t key_ld = key_ok ? key : tc.doc_end - 1;
   const int key_rel = (int)(key - q_begin);  // position of the key among the rows that see the tile
+  // dS workspace (STORE_DS): this lane's 32-byte slot inside the block of the step's (query head, query
+  // tile), for 32-query block 0 (block rb adds 2048); the block itself is located once per step (ds_step)
+  const uint32_t ds_lane = (uint32_t)(k0 / 32 + wv) * 8192u + (uint32_t)h * 1024u + (uint32_t)((n ^ (h << 2)) << 5);
+  // (dense input, S a multiple of 128: query tile it = k0 / BK + tile_idx; consecutive blocks of a head are
+  // 32768 (it + 1) bytes apart, heads ds_head bytes)
+  const int64_t ds_head = STORE_DS ? ds_matrix_offset(p.S / BQ, 1, 0) : 0;
+  char* ds_first = STORE_DS ? reinterpret_cast<char*>(p.ds) + ds_matrix_offset(p.S / BQ, (int64_t)tc.b * p.Hq + g * group, k0 / BK)
+                            : nullptr;   // first step of the current query head
+  char* ds_step = ds_first;
   bf16x8 kf[NKS], vf[NKS];                   // live in AGPRs
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
@@ -449,8 +458,18 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     };
     auto spread = [&](int slot_idx) __attribute__((always_inline)) {   // 4 * NB slots per tile
       if (kSpread) {
-        if (slot_idx < kPieces) copy_piece(next, slot_idx);
-        if (slot_idx + 4 * NB < kPieces) copy_piece(next, slot_idx + 4 * NB);
+        if (STORE_DS) {
+          // all copies in the first two blocks, ahead of the second block's dS stores: the step's final wait
+          // then leaves only stores open (see step_fn)
+          constexpr int kSlots = 8;
+          if (slot_idx < kSlots) {
+#pragma unroll
+            for (int k = slot_idx; k < kPieces; k += kSlots) copy_piece(next, k);
+          }
+        } else {
+          if (slot_idx < kPieces) copy_piece(next, slot_idx);
+          if (slot_idx + 4 * NB < kPieces) copy_piece(next, slot_idx + 4 * NB);
+        }
       }
     };
 
@@ -536,6 +555,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
       }
       dsf0 = frag_from_words(dw[0], dw[1], dw[2], dw[3]);
       dsf1 = frag_from_words(dw[4], dw[5], dw[6], dw[7]);
+      if (STORE_DS) {   // read once by the next kernel: no reason to keep the lines in L2
+        char* dst = ds_step + ds_lane + rb * 2048;
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, dsf0), reinterpret_cast<u32x4*>(dst));
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, dsf1), reinterpret_cast<u32x4*>(dst + 16));
+      }
     }
     pending = true;
   };
@@ -624,6 +648,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
         }
         dsf[sblk] = cat_pairs(dd[0], dd[1], dd[2], dd[3]);
       }
+      if (STORE_DS) {   // masked elements are exact zeros (p = exp2(-inf))
+        char* dst = ds_step + ds_lane + rb * 2048;
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, dsf[0]), reinterpret_cast<u32x4*>(dst));
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, dsf[1]), reinterpret_cast<u32x4*>(dst + 16));
+      }
       if (rb + 1 < NB) {
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) qn[ks] = lds_read8(sp_.nat[ks], blk + 32 * ROW_BYTES);
@@ -667,11 +696,19 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     const uint64_t tt1 = __builtin_readcyclecounter();
     if (fast) { t_fast += tt1 - tt0; n_fast += 1; } else { t_gen += tt1 - tt0; }
 #endif
-    async_wait_all();
+    // The next tile's copies have landed; vector memory operations complete in issue order, and after a
+    // hand-sequenced tile that copied piece by piece the six youngest are the dS stores of its last three
+    // 32-row blocks, which nothing in this kernel waits for.
+    if (STORE_DS && fast && next_full) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else async_wait_all();
     __syncthreads();
 #ifdef IE_EXP_TIMING
     t_sync += __builtin_readcyclecounter() - tt1;
 #endif
+    if (STORE_DS) {
+      if (next_tile == 0) { ds_first += ds_head; ds_step = ds_first; }
+      else ds_step += (int64_t)((int)(k0 / BK) + next_tile) * 32768;
+    }
     hq_idx = next_hq;
     tile_idx = next_tile;
   };
@@ -710,6 +747,128 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   }  // next item
 }
 
+// ---- dQ from a materialised dS ---------------------------------------------------------------
+// When the caller's workspace has room for dS (attn_common.hpp: ds_matrix_offset), the dK/dV kernel
+// stores the dS it forms anyway and dQ = scale * dS K is a plain product: one third of the dQ
+// kernel's matrix work, paid for with one write and one read of dS (Hq * S^2 bytes for causal input).
+// The kernel is bound by that read, so it is built as a stream: 32-key stages (the K rows and the dS
+// rows of the item's matrix, both 256-byte rows) in a ring of four, three stages in flight per
+// workgroup and two workgroups per CU.  dS arrives with the key index slowest, the order the dK/dV kernel
+// holds it in, and K is key-major too, so both operands of dQ^T += K^T dS^T are gathered with transpose loads;
+// wave w owns the columns of 32-query block w (a permutation of the tile's queries 32w .. 32w+31).
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnParams p) {
+  static_assert(D == 128, "the dS workspace is laid out for head dimension 128");
+  constexpr int BM = 128, BN = 32, NS = 4;
+  constexpr int NDB = D / 32;
+  constexpr int ROW_BYTES = D * 2;
+  constexpr int TILE_BYTES = BN * ROW_BYTES;
+  constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K rows, dS rows
+  constexpr int PIECES = BN / 16;              // copy instructions per wave and tile
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ int scratch[8];
+
+  __shared__ int s_work;
+  const uint32_t xcc = xcc_id();
+  int skip = 0;
+  for (;;) {   // persistent: one item (batch, head, query tile) per iteration (tile_queue.hpp)
+  const int item = next_work(p, &s_work, xcc, skip);
+  if (item < 0) break;
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wv = tid >> 6;
+  const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
+
+  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item);
+  if (!tc.valid) continue;
+  const int g = tc.h / (p.Hq / p.Hkv);
+  const int64_t q0 = tc.t0;
+  const int it = (int)(q0 / BM);
+  const int nkt = (it + 1) * (BM / BN);   // stages: keys 0 .. q0 + 127, a multiple of NS
+
+  const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
+  const char* kbase = reinterpret_cast<const char*>(p.k + ((int64_t)tc.b * p.S * p.Hkv + g) * D);
+  const char* sbase = reinterpret_cast<const char*>(p.ds) + ds_matrix_offset(p.S / BM, (int64_t)tc.b * p.Hq + tc.h, it);
+
+  const uint32_t lds0 = lds_address(smem);
+  AsyncTile<D> ldk;
+  ldk.init(tid, kv_pitch);
+  const int wave_u = ldk.wave;
+  auto issue = [&](const int kt, const int slot) __attribute__((always_inline)) {
+    const uint32_t dst = lds0 + slot * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+      ldk.load_full_piece(dst, kbase + (int64_t)kt * BN * kv_pitch, i);
+      // the 32-key group of dS, as it lies in memory
+      async_copy16((uint32_t)lane * 16u, sbase + (int64_t)kt * TILE_BYTES + (i * 4 + wave_u) * 1024,
+                   dst + TILE_BYTES + (i * 4 + wave_u) * 1024);
+    }
+  };
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) issue(t, t);
+
+  const char* tr_k0[NDB];   // K^T fragments: keys 4 (grp / 2) .. +3 and 8 + ..., columns 32 db + lane % 32
+  const char* tr_k8[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    tr_k0[db] = smem + tr_off<D>(lane, 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+    tr_k8[db] = smem + tr_off<D>(lane, 8 + 4 * (grp >> 1), 32 * db + 16 * (grp & 1));
+  }
+  // dS^T fragments of the wave's columns: lane L of a 16-lane group addresses key r0 + L / 4, values 4 (L % 4) .. +3
+  // of half-wave slot hh = grp & 1 (see the workspace layout in attn_common.hpp)
+  const int hh = grp & 1, l16 = lane & 15;
+  const char* tr_s0 = smem + TILE_BYTES + wv * 2048 + hh * 1024 + ((((4 * (grp >> 1)) ^ (4 * hh)) + (l16 >> 2)) << 5) + ((l16 & 3) << 3);
+  const char* tr_s8 = smem + TILE_BYTES + wv * 2048 + hh * 1024 + ((((8 + 4 * (grp >> 1)) ^ (4 * hh)) + (l16 >> 2)) << 5) + ((l16 & 3) << 3);
+
+  f32x16 acc[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+  // the copies of tile t+1 have landed when at most the PIECES * 2 * (NS - 2) instructions issued after them are open
+  auto wait_next = [&](const bool issued) __attribute__((always_inline)) {
+    static_assert(2 * PIECES * (NS - 2) == 8, "the immediate below");
+    if (issued) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else async_wait_all();
+  };
+  auto step = [&](const int kt, auto slot_c) __attribute__((always_inline)) {
+    constexpr int slot = decltype(slot_c)::value;
+    const bool more = kt + NS - 1 < nkt;
+    if (more) issue(kt + NS - 1, (slot + NS - 1) % NS);   // the stage consumed in the previous step
+#pragma unroll
+    for (int ks = 0; ks < BN / 16; ++ks) {
+      const int off = slot * STAGE_BYTES + 16 * ks * ROW_BYTES;
+      const int soff = slot * STAGE_BYTES + 16 * ks * 32;   // 32 bytes per key inside a (block, half-wave) slot group
+      const bf16x8 dst_ = cat4(lds_read_tr4(tr_s0 + soff), lds_read_tr4(tr_s8 + soff));
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        const bf16x8 ktf = cat4(lds_read_tr4(tr_k0[db] + off), lds_read_tr4(tr_k8[db] + off));
+        acc[db] = mfma32(ktf, dst_, acc[db]);
+      }
+    }
+    wait_next(more);
+    __syncthreads();
+  };
+
+  wait_next(true);
+  __syncthreads();
+  for (int kt = 0; kt < nkt; kt += NS) {
+    step(kt, std::integral_constant<int, 0>{});
+    step(kt + 1, std::integral_constant<int, 1>{});
+    step(kt + 2, std::integral_constant<int, 2>{});
+    step(kt + 3, std::integral_constant<int, 3>{});
+  }
+
+  // column 32 wv + n of the matrix is query 32 wv + 8 (e / 4) + 4 hh + e % 4 with hh = n / 16, e = n % 16
+  const int e = n & 15;
+  const int64_t row = q0 + 32 * wv + 8 * (e >> 2) + 4 * (n >> 4) + (e & 3);
+  __bf16* drow = p.dq + (((int64_t)tc.b * p.S + row) * p.Hq + tc.h) * D;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc[db], p.scale, h, true);
+  }  // next item
+}
+
 template <int D>
 static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
   hipError_t e;
@@ -720,33 +879,63 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     attn_bwd_delta_kernel<D><<<dim3((unsigned)grid), dim3(kThreads), 0, st>>>(p);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
   }
-  if (phases & 2) {  // dq
-    constexpr int smem = 2 * 2 * 64 * D * 2;
-    int rc = set_smem(attn_bwd_dq_kernel<D>, smem);
-    if (rc) return rc;
+  // With room for dS in the workspace (p.ds), dK/dV runs first and stores it, and dQ is one product.
+  const bool from_ds = p.ds != nullptr;
+  auto dq_phase = [&]() -> int {
     int64_t tiles = tiles_per_head(p.S, 128, p.cu, p.num_docs);
     int64_t items = tiles * p.B * p.Hq;
     if (items >= ((int64_t)1 << 31)) return kErrShape;
-    p.tiles = (int32_t)tiles;
+    AttnParams a = p;
+    a.tiles = (int32_t)tiles;
+    if constexpr (D == 128) {
+      if (from_ds) {
+        constexpr int smem = 4 * 2 * 32 * D * 2;
+        int rc = set_smem(attn_bwd_dq_from_ds_kernel<D>, smem);
+        if (rc) return rc;
+        static const int per_cu = resident_per_cu(attn_bwd_dq_from_ds_kernel<D>, smem);
+        const QueueLaunch ql = tile_queue_prepare(a, items, a.Hq, per_cu, st);
+        if (ql.err != hipSuccess) return hip_fail(ql.err);
+        attn_bwd_dq_from_ds_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
+        if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
+        return 0;
+      }
+    }
+    constexpr int smem = 2 * 2 * 64 * D * 2;
+    int rc = set_smem(attn_bwd_dq_kernel<D>, smem);
+    if (rc) return rc;
     static const int per_cu = resident_per_cu(attn_bwd_dq_kernel<D>, smem);
-    const QueueLaunch ql = tile_queue_prepare(p, items, p.Hq, per_cu, st);
+    const QueueLaunch ql = tile_queue_prepare(a, items, a.Hq, per_cu, st);
     if (ql.err != hipSuccess) return hip_fail(ql.err);
-    attn_bwd_dq_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
+    attn_bwd_dq_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
-  }
-  if (phases & 4) {  // dk, dv
+    return 0;
+  };
+  auto dkdv_phase = [&](auto store_c) -> int {
+    constexpr bool kStore = decltype(store_c)::value;
     constexpr int smem = DkdvCfg<D>::SMEM_BYTES;
-    int rc = set_smem(attn_bwd_dkdv_kernel<D>, smem);
+    int rc = set_smem(attn_bwd_dkdv_kernel<D, kStore>, smem);
     if (rc) return rc;
     int64_t tiles = tiles_per_head(p.S, 128, p.cu, p.num_docs);
     int64_t items = tiles * p.B * p.Hkv;
     if (items >= ((int64_t)1 << 31)) return kErrShape;
-    p.tiles = (int32_t)tiles;
-    static const int per_cu = resident_per_cu(attn_bwd_dkdv_kernel<D>, smem);
-    const QueueLaunch ql = tile_queue_prepare(p, items, p.Hkv, per_cu, st);
+    AttnParams a = p;
+    a.tiles = (int32_t)tiles;
+    static const int per_cu = resident_per_cu(attn_bwd_dkdv_kernel<D, kStore>, smem);
+    const QueueLaunch ql = tile_queue_prepare(a, items, a.Hkv, per_cu, st);
     if (ql.err != hipSuccess) return hip_fail(ql.err);
-    attn_bwd_dkdv_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
+    attn_bwd_dkdv_kernel<D, kStore><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
+    return 0;
+  };
+  int rc = 0;
+  if (from_ds) {
+    if constexpr (D == 128) {
+      if ((phases & 4) && (rc = dkdv_phase(std::true_type{}))) return rc;
+    }
+    if ((phases & 2) && (rc = dq_phase())) return rc;
+  } else {
+    if ((phases & 2) && (rc = dq_phase())) return rc;
+    if ((phases & 4) && (rc = dkdv_phase(std::false_type{}))) return rc;
   }
   return 0;
 }

@@ -80,6 +80,20 @@ size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv
   return 2 * align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256);  // delta and lse*log2e, [B,Hq,S] each
 }
 
+// dS of causal dense input: per (batch, query head) the lower block triangle of 128 x 128 blocks, bf16.
+static size_t ds_bytes(int64_t B, int64_t S, int32_t Hq) {
+  const size_t nt = (size_t)(S / 128);
+  return (size_t)B * (size_t)Hq * (nt * (nt + 1) / 2) * 32768;
+}
+
+size_t ie_attn_bwd_fast_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs,
+                                        int32_t causal) {
+  const size_t base = ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs);
+  if (base == 0 || num_docs != 0 || causal != 1 || D != 128 || S % 128 != 0) return base;
+  if ((double)B * Hq * ((double)S / 128) * ((double)S / 128 + 1) / 2 * 32768 > 1e15) return base;
+  return base + ds_bytes(B, S, Hq);
+}
+
 int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
                 void* dq, void* dk, void* dv, const int32_t* cu_seqlens, int32_t num_docs, int64_t B, int64_t S,
                 int32_t Hq, int32_t Hkv, int32_t D, float scale, int32_t causal, void* workspace,
@@ -107,6 +121,9 @@ int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* 
   p.lse = lse;
   p.delta = static_cast<float*>(workspace);
   p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 2);
+  // A workspace with room for dS selects the path that stores it (only dense causal input has one).
+  const size_t fast = cu_seqlens ? need : ie_attn_bwd_fast_workspace_bytes(B, S, Hq, Hkv, D, 0, causal);
+  p.ds = (fast > need && workspace_bytes >= fast) ? reinterpret_cast<__bf16*>(static_cast<char*>(workspace) + need) : nullptr;
   p.dq = static_cast<__bf16*>(dq);
   p.dk = static_cast<__bf16*>(dk);
   p.dv = static_cast<__bf16*>(dv);

@@ -20,7 +20,8 @@ def w64(t):
     return np.ascontiguousarray(t.to("cpu", torch.float32).numpy().astype(np.float64))
 
 
-def run_full(cfg):
+def run_full(cfg, stored_ds=False):
+    """stored_ds: the backward path bench.py times where the shape has it (a workspace with room for dS)."""
     from paper_2401_09149_amd import binding, workloads as W
     cu = W.make_cu_seqlens(cfg)
     q, k, v, do = W.make_inputs(cfg)
@@ -28,8 +29,12 @@ def run_full(cfg):
     qd, kd, vd, dod = (x.to(dev) for x in (q, k, v, do))
     cud = None if cu is None else torch.tensor(cu, dtype=torch.int32, device=dev)
     o, lse = binding.attn_fwd(qd, kd, vd, cfg.scale, cfg.causal, cud)
-    dq, dk, dv = binding.attn_bwd(qd, kd, vd, o, dod, lse, cfg.scale, cfg.causal, cud)
+    ws = binding.alloc_bwd_workspace(qd, kd, cud, fast=stored_ds, causal=cfg.causal)
+    if stored_ds:
+        assert ws.numel() > binding.alloc_bwd_workspace(qd, kd, cud).numel()
+    dq, dk, dv = binding.attn_bwd(qd, kd, vd, o, dod, lse, cfg.scale, cfg.causal, cud, workspace=ws)
     torch.cuda.synchronize()
+    del ws
     return cu, (q, k, v, do), (qd, kd, vd, dod), (o, lse, dq, dk, dv)
 
 
@@ -98,10 +103,11 @@ def check_identities(cfg, cu, gpu_in, gpu_out):
         assert float((s.abs() / n.clamp_min(1e-30)).max()) <= 5e-3
 
 
-def test_config1_s32k_h32(oracle):
+@pytest.mark.parametrize("stored_ds", [True, False])
+def test_config1_s32k_h32(oracle, stored_ds):
     from paper_2401_09149_amd import workloads as W
     cfg = W.CONFIGS[1]
-    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg, stored_ds)
     S = cfg.S
     check_rows(oracle, cfg, cu, cpu_in, gpu_out, 0, [(0, 40), (8180, 8200), (S - 33, S)])
     check_rows(oracle, cfg, cu, cpu_in, gpu_out, 31, [(16370, 16400)])
@@ -131,10 +137,11 @@ def test_config2_s128k_h8(oracle):
     check_identities(cfg, cu, gpu_in, gpu_out)
 
 
-def test_config3_gqa_s64k(oracle):
+@pytest.mark.parametrize("stored_ds", [True, False])
+def test_config3_gqa_s64k(oracle, stored_ds):
     from paper_2401_09149_amd import workloads as W
     cfg = W.CONFIGS[3]
-    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg, stored_ds)
     S = cfg.S
     check_rows(oracle, cfg, cu, cpu_in, gpu_out, 0, [(0, 20), (S - 20, S)])
     check_rows(oracle, cfg, cu, cpu_in, gpu_out, 7, [(32760, 32780)])
