@@ -751,27 +751,28 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 // When the caller's workspace has room for dS (attn_common.hpp: ds_matrix_offset), the dK/dV kernel
 // stores the dS it forms anyway and dQ = scale * dS K is a plain product: one third of the dQ
 // kernel's matrix work, paid for with one write and one read of dS (Hq * S^2 bytes for causal input).
-// The kernel is bound by that read, so it is built as a stream: 32-key stages (the K rows and the dS
-// rows of the item's matrix, both 256-byte rows) in a ring of four, three stages in flight per
-// workgroup and two workgroups per CU.  dS arrives with the key index slowest, the order the dK/dV kernel
-// holds it in, and K is key-major too, so both operands of dQ^T += K^T dS^T are gathered with transpose loads;
-// wave w owns the columns of 32-query block w (a permutation of the tile's queries 32w .. 32w+31).
+// The kernel is bound by that read, so it is built as a stream: a workgroup owns TWO 128-query tiles
+// (so that K is fetched once for both), 32-key stages (K rows and both tiles' dS groups, 8 KiB each) in a
+// ring of three, two in flight per workgroup and two workgroups per CU.  dS arrives with the key index
+// slowest, the order the dK/dV kernel holds it in, and K is key-major too, so both operands of
+// dQ^T += K^T dS^T are gathered with transpose loads; wave w owns the columns of 32-query block w of both
+// tiles (a permutation of the tiles' queries 32w .. 32w+31), and every K^T fragment feeds both.
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnParams p) {
   static_assert(D == 128, "the dS workspace is laid out for head dimension 128");
-  constexpr int BM = 128, BN = 32, NS = 4;
+  constexpr int BM = 256, BN = 32, NS = 3;
   constexpr int NDB = D / 32;
   constexpr int ROW_BYTES = D * 2;
-  constexpr int TILE_BYTES = BN * ROW_BYTES;
-  constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K rows, dS rows
-  constexpr int PIECES = BN / 16;              // copy instructions per wave and tile
+  constexpr int TILE_BYTES = BN * ROW_BYTES;   // K rows of a stage; also one tile's dS group
+  constexpr int STAGE_BYTES = 3 * TILE_BYTES;  // K, dS of the first tile, dS of the second
+  constexpr int PIECES = BN / 16;              // copy instructions per wave and 8 KiB
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
   __shared__ int s_work;
   const uint32_t xcc = xcc_id();
   int skip = 0;
-  for (;;) {   // persistent: one item (batch, head, query tile) per iteration (tile_queue.hpp)
+  for (;;) {   // persistent: one item (batch, head, pair of query tiles) per iteration (tile_queue.hpp)
   const int item = next_work(p, &s_work, xcc, skip);
   if (item < 0) break;
   int tid = threadIdx.x;
@@ -783,25 +784,33 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
   if (!tc.valid) continue;
   const int g = tc.h / (p.Hq / p.Hkv);
   const int64_t q0 = tc.t0;
-  const int it = (int)(q0 / BM);
-  const int nkt = (it + 1) * (BM / BN);   // stages: keys 0 .. q0 + 127, a multiple of NS
+  const int ita = (int)(q0 / 128);                // first tile; the second is ita + 1 unless S ends before it
+  const bool has_b = q0 + 128 < p.S;
+  const int nkt_a = (ita + 1) * (128 / BN);       // stages the first tile takes part in
+  const int nkt = has_b ? nkt_a + 128 / BN : nkt_a;
 
   const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
   const char* kbase = reinterpret_cast<const char*>(p.k + ((int64_t)tc.b * p.S * p.Hkv + g) * D);
-  const char* sbase = reinterpret_cast<const char*>(p.ds) + ds_matrix_offset(p.S / BM, (int64_t)tc.b * p.Hq + tc.h, it);
+  const int64_t bh = (int64_t)tc.b * p.Hq + tc.h;
+  const char* sa = reinterpret_cast<const char*>(p.ds) + ds_matrix_offset(p.S / 128, bh, ita);
+  const char* sb = has_b ? sa + (int64_t)(ita + 1) * 32768 : sa;   // (without a second tile: valid memory, never used)
 
   const uint32_t lds0 = lds_address(smem);
   AsyncTile<D> ldk;
   ldk.init(tid, kv_pitch);
   const int wave_u = ldk.wave;
+  // Every stage issues the same six instructions per wave, so that the waits below can count them: past the
+  // first tile's last stage its copy repeats that stage (8 KiB that nobody reads, four times per item).
   auto issue = [&](const int kt, const int slot) __attribute__((always_inline)) {
     const uint32_t dst = lds0 + slot * STAGE_BYTES;
+    const int kta = kt < nkt_a ? kt : nkt_a - 1;
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
+      const int piece = (i * 4 + wave_u) * 1024;
       ldk.load_full_piece(dst, kbase + (int64_t)kt * BN * kv_pitch, i);
-      // the 32-key group of dS, as it lies in memory
-      async_copy16((uint32_t)lane * 16u, sbase + (int64_t)kt * TILE_BYTES + (i * 4 + wave_u) * 1024,
-                   dst + TILE_BYTES + (i * 4 + wave_u) * 1024);
+      // the 32-key groups of dS, as they lie in memory
+      async_copy16((uint32_t)lane * 16u, sa + (int64_t)kta * TILE_BYTES + piece, dst + TILE_BYTES + piece);
+      async_copy16((uint32_t)lane * 16u, sb + (int64_t)kt * TILE_BYTES + piece, dst + 2 * TILE_BYTES + piece);
     }
   };
 #pragma unroll
@@ -820,31 +829,39 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
   const char* tr_s0 = smem + TILE_BYTES + wv * 2048 + hh * 1024 + ((((4 * (grp >> 1)) ^ (4 * hh)) + (l16 >> 2)) << 5) + ((l16 & 3) << 3);
   const char* tr_s8 = smem + TILE_BYTES + wv * 2048 + hh * 1024 + ((((8 + 4 * (grp >> 1)) ^ (4 * hh)) + (l16 >> 2)) << 5) + ((l16 & 3) << 3);
 
-  f32x16 acc[NDB];
+  f32x16 acc_a[NDB], acc_b[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+    for (int r = 0; r < 16; ++r) { acc_a[db][r] = 0.f; acc_b[db][r] = 0.f; }
 
-  // the copies of tile t+1 have landed when at most the PIECES * 2 * (NS - 2) instructions issued after them are open
+  // the copies of stage t+1 have landed when at most the 3 * PIECES * (NS - 2) instructions issued after them are open
   auto wait_next = [&](const bool issued) __attribute__((always_inline)) {
-    static_assert(2 * PIECES * (NS - 2) == 8, "the immediate below");
-    if (issued) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    static_assert(3 * PIECES * (NS - 2) == 6, "the immediate below");
+    if (issued) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
     else async_wait_all();
   };
   auto step = [&](const int kt, auto slot_c) __attribute__((always_inline)) {
     constexpr int slot = decltype(slot_c)::value;
     const bool more = kt + NS - 1 < nkt;
     if (more) issue(kt + NS - 1, (slot + NS - 1) % NS);   // the stage consumed in the previous step
+    const bool do_a = kt < nkt_a;
 #pragma unroll
     for (int ks = 0; ks < BN / 16; ++ks) {
       const int off = slot * STAGE_BYTES + 16 * ks * ROW_BYTES;
       const int soff = slot * STAGE_BYTES + 16 * ks * 32;   // 32 bytes per key inside a (block, half-wave) slot group
-      const bf16x8 dst_ = cat4(lds_read_tr4(tr_s0 + soff), lds_read_tr4(tr_s8 + soff));
+      bf16x8 ktf[NDB];
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        const bf16x8 ktf = cat4(lds_read_tr4(tr_k0[db] + off), lds_read_tr4(tr_k8[db] + off));
-        acc[db] = mfma32(ktf, dst_, acc[db]);
+      for (int db = 0; db < NDB; ++db) ktf[db] = cat4(lds_read_tr4(tr_k0[db] + off), lds_read_tr4(tr_k8[db] + off));
+      if (do_a) {
+        const bf16x8 dsa = cat4(lds_read_tr4(tr_s0 + soff), lds_read_tr4(tr_s8 + soff));
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) acc_a[db] = mfma32(ktf[db], dsa, acc_a[db]);
+      }
+      if (has_b) {
+        const bf16x8 dsb = cat4(lds_read_tr4(tr_s0 + soff + TILE_BYTES), lds_read_tr4(tr_s8 + soff + TILE_BYTES));
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) acc_b[db] = mfma32(ktf[db], dsb, acc_b[db]);
       }
     }
     wait_next(more);
@@ -853,19 +870,24 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
 
   wait_next(true);
   __syncthreads();
-  for (int kt = 0; kt < nkt; kt += NS) {
+  int kt = 0;
+  for (; kt + NS <= nkt; kt += NS) {
     step(kt, std::integral_constant<int, 0>{});
     step(kt + 1, std::integral_constant<int, 1>{});
     step(kt + 2, std::integral_constant<int, 2>{});
-    step(kt + 3, std::integral_constant<int, 3>{});
   }
+  if (kt < nkt) step(kt, std::integral_constant<int, 0>{});
+  if (kt + 1 < nkt) step(kt + 1, std::integral_constant<int, 1>{});
 
-  // column 32 wv + n of the matrix is query 32 wv + 8 (e / 4) + 4 hh + e % 4 with hh = n / 16, e = n % 16
+  // column 32 wv + n of a tile is its query 32 wv + 8 (e / 4) + 4 hh + e % 4 with hh = n / 16, e = n % 16
   const int e = n & 15;
   const int64_t row = q0 + 32 * wv + 8 * (e >> 2) + 4 * (n >> 4) + (e & 3);
   __bf16* drow = p.dq + (((int64_t)tc.b * p.S + row) * p.Hq + tc.h) * D;
 #pragma unroll
-  for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc[db], p.scale, h, true);
+  for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc_a[db], p.scale, h, true);
+  drow += (int64_t)128 * p.Hq * D;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc_b[db], p.scale, h, has_b);
   }  // next item
 }
 
@@ -882,14 +904,14 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
   // With room for dS in the workspace (p.ds), dK/dV runs first and stores it, and dQ is one product.
   const bool from_ds = p.ds != nullptr;
   auto dq_phase = [&]() -> int {
-    int64_t tiles = tiles_per_head(p.S, 128, p.cu, p.num_docs);
+    int64_t tiles = tiles_per_head(p.S, from_ds ? 256 : 128, p.cu, p.num_docs);
     int64_t items = tiles * p.B * p.Hq;
     if (items >= ((int64_t)1 << 31)) return kErrShape;
     AttnParams a = p;
     a.tiles = (int32_t)tiles;
     if constexpr (D == 128) {
       if (from_ds) {
-        constexpr int smem = 4 * 2 * 32 * D * 2;
+        constexpr int smem = 3 * 3 * 32 * D * 2;
         int rc = set_smem(attn_bwd_dq_from_ds_kernel<D>, smem);
         if (rc) return rc;
         static const int per_cu = resident_per_cu(attn_bwd_dq_from_ds_kernel<D>, smem);
