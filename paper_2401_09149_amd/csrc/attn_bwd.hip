@@ -809,8 +809,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
       const int piece = (i * 4 + wave_u) * 1024;
       ldk.load_full_piece(dst, kbase + (int64_t)kt * BN * kv_pitch, i);
       // the 32-key groups of dS, as they lie in memory
-      async_copy16((uint32_t)lane * 16u, sa + (int64_t)kta * TILE_BYTES + piece, dst + TILE_BYTES + piece);
-      async_copy16((uint32_t)lane * 16u, sb + (int64_t)kt * TILE_BYTES + piece, dst + 2 * TILE_BYTES + piece);
+      async_copy16_stream((uint32_t)lane * 16u, sa + (int64_t)kta * TILE_BYTES + piece, dst + TILE_BYTES + piece);
+      async_copy16_stream((uint32_t)lane * 16u, sb + (int64_t)kt * TILE_BYTES + piece, dst + 2 * TILE_BYTES + piece);
     }
   };
 #pragma unroll

@@ -289,6 +289,15 @@ __device__ __forceinline__ void async_copy16(uint32_t voffset, const char* sbase
                : "v"(voffset), "s"(sbase), "s"(lds_addr)
                : "memory");
 }
+// The same for data that is read once (non-temporal: the lines are the first to leave L2 again).
+__device__ __forceinline__ void async_copy16_stream(uint32_t voffset, const char* sbase, uint32_t lds_addr) {
+  sbase = uniform(sbase);
+  lds_addr = uniform(lds_addr);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+               :
+               : "v"(voffset), "s"(sbase), "s"(lds_addr)
+               : "memory");
+}
 __device__ __forceinline__ void async_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Makes the compiler treat `x` as consumed here, so that the wait for the global load that

@@ -90,7 +90,8 @@ size_t ie_attn_bwd_fast_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_
                                         int32_t causal) {
   const size_t base = ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs);
   if (base == 0 || num_docs != 0 || causal != 1 || D != 128 || S % 128 != 0) return base;
-  if ((double)B * Hq * ((double)S / 128) * ((double)S / 128 + 1) / 2 * 32768 > 1e15) return base;
+  // (the kernels keep byte offsets inside one query tile's block in 32 bits: 256 S bytes; and no device holds 2^50)
+  if (S >= ((int64_t)1 << 23) || (double)B * Hq * (double)S * ((double)S + 128) > 1e15) return base;
   return base + ds_bytes(B, S, Hq);
 }
 

@@ -4,7 +4,9 @@ The paper's computation profiler measures `self-atten(b, S, H, D/s_sp)` on a sin
 shapes its planner considers (Sec. 4.2 "Computation Profiler"); this is that sweep for the plans
 the paper lists as its own choice ("Our Work" rows of Appendix Tables 4-7): micro-batch b, all S
 tokens, heads/s_sp heads of dimension 128 (Table 1: 32, 40, 48 and 64 heads).  Inputs are N(0,1)
-rounded to bf16, drawn on the device (timing only; parity is the tests' business).
+rounded to bf16, drawn on the device (timing only; parity is the tests' business).  The backward pass is
+timed twice: with the small workspace (dQ recomputes S, P, dP) and, where B*Hq*S*(S+128) bytes more fit the
+limit given by --ds-limit-gb, with the workspace that lets the dK/dV kernel store dS.
 
     python -m paper_2401_09149_amd.self_atten_sweep [--iters 5] [--out profiles/self_atten_sweep.md]
 """
@@ -33,6 +35,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=5)
     ap.add_argument("--out", default=None, help="also write the table (markdown) to this file")
+    ap.add_argument("--ds-limit-gb", type=float, default=160.0, help="largest workspace for the stored-dS backward path")
     args = ap.parse_args()
     import torch
     from . import binding
@@ -45,8 +48,8 @@ def main():
     gen.manual_seed(1)
     D = HEAD_DIM
     scale = D ** -0.5
-    lines = ["| model | S | b | s_sp | heads/GPU | fwd ms | fwd TFLOP/s | bwd ms | bwd TFLOP/s | fwd+bwd % of 2.5 PFLOP/s |",
-             "|---|---|---|---|---|---|---|---|---|---|"]
+    lines = ["| model | S | b | s_sp | heads/GPU | fwd ms | fwd TFLOP/s | bwd ms | bwd TFLOP/s | bwd ms, stored dS | workspace GB | fwd+bwd % of 2.5 PFLOP/s (faster bwd) |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|"]
     for model, S, b, s_sp, H in shapes():
         mk = lambda: torch.randn((b, S, H, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
         q, k, v, do = mk(), mk(), mk(), mk()
@@ -69,10 +72,17 @@ def main():
             return e0.elapsed_time(e1) / args.iters
 
         f_ms, b_ms = timed(fwd), timed(bwd)
+        big = binding.ie_attn_bwd_fast_workspace_bytes(b, S, H, H, D, 0, True)
+        s_ms = None
+        if ws.numel() < big <= args.ds_limit_gb * 1e9:
+            del ws
+            ws = torch.empty(big, dtype=torch.uint8, device=dev)
+            s_ms = timed(bwd)
         flop_f = 2.0 * b * H * float(S) ** 2 * D   # 4 S^2 D H / 2 (causal halving); backward = 2.5x
         tf_f, tf_b = flop_f / f_ms / 1e9, 2.5 * flop_f / b_ms / 1e9
-        both = 3.5 * flop_f / (f_ms + b_ms) / 1e9
+        both = 3.5 * flop_f / (f_ms + min(b_ms, s_ms or b_ms)) / 1e9
         line = (f"| {model} | {S} | {b} | {s_sp} | {H} | {f_ms:.3f} | {tf_f:.0f} | {b_ms:.3f} | {tf_b:.0f} | "
+                f"{'—' if s_ms is None else format(s_ms, '.3f')} | {'—' if s_ms is None else format(big / 1e9, '.1f')} | "
                 f"{100 * both / PEAK_BF16_TFLOPS:.1f} |")
         print(line, flush=True)
         lines.append(line)
