@@ -151,7 +151,7 @@ def sp_permute_bench(cfg, iters, with_cpu, profiled_with):
     return out
 
 
-def linear_bench(iters, with_cpu):
+def linear_bench(iters, with_cpu, profiled_with):
     """The linear modules of one 7B layer (hidden 4096, MLP 11008; Table 1) applied to one GPU's 8192 tokens of the
     paper's 32K plan (s_sp = 4): forward, input gradient and weight gradient of the QKV, output, gate/up and down
     projections.  FLOP = 2 M N K per product.  torch.matmul (the vendor library) on the same operands is timed
@@ -196,8 +196,8 @@ def linear_bench(iters, with_cpu):
            "order": ["fwd", "bwd_input", "bwd_weight"], "per_module": per, "ms_per_layer": ms_total,
            "library_ms_per_layer": lib_ms_total,
            "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                        "note": "all twelve products of one layer: FLOP / time"}}
+                        "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(profiled_with, "linear_gemm_kernel"),
+                        "note": "all twelve products of one layer: FLOP / time; traffic: HBM bytes per launch, mean over the twelve"}}
     if with_cpu:
         import numpy as np
         from oracle import linear as ora
@@ -351,7 +351,7 @@ def main():
     if not args.no_linear:
         if args.sp_config < 0:
             del q, k, v, dout, o, lse, dq, dk, dv, ws
-        out["linear"] = linear_bench(it, not args.no_cpu_baseline)
+        out["linear"] = linear_bench(it, not args.no_cpu_baseline, cfg.name)
     print(json.dumps(out))
 
 
