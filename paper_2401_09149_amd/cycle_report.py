@@ -43,7 +43,7 @@ def measure(which):
     o = torch.empty_like(q)
     lse = torch.zeros((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device=dev)
     dq, dk, dv = torch.zeros_like(q), torch.empty_like(k), torch.empty_like(v)
-    ws = binding.alloc_bwd_workspace(q, k, None)
+    ws = binding.alloc_bwd_workspace(q, k, None, fast=(which == "dkdv_ds"))   # dkdv_ds: the variant that stores dS
     fwd = lambda: binding.ie_attn_fwd(q, k, v, o, lse, None, cfg.scale, True)
     bwd = lambda ph: binding.ie_attn_bwd_phases(q, k, v, o, do, lse, dq, dk, dv, None, cfg.scale, True, ws, ph)
 
@@ -77,7 +77,7 @@ def measure(which):
         d = dq.view(torch.int64).flatten()[: n * 8].cpu().numpy().reshape(n, 8).astype(float)
         tot, tf, nf, tg, ts, steps, tready = (d[:, i] for i in range(7))
         clock = tot.sum() / 256 / (ms * 1e-3) / 1e9   # one workgroup per CU at a time, 256 CUs, all busy
-        print(f"dK/dV: {ms:.3f} ms, shader clock about {clock:.2f} GHz (sum of workgroup cycles / 256 CUs / time), "
+        print(f"dK/dV{' with dS stores' if which == 'dkdv_ds' else ''}: {ms:.3f} ms, shader clock about {clock:.2f} GHz (sum of workgroup cycles / 256 CUs / time), "
               f"{tf.sum() / nf.sum() / 128:.1f} cycles per MFMA in the hand-sequenced tiles ({int(nf.sum())} of {int(steps.sum())} steps), "
               f"{ts.sum() / steps.sum():.0f} cycles per step at the barrier; per workgroup {tf.mean():.0f} cycles in hand-sequenced "
               f"tiles, {tg.mean():.0f} in masked tiles, {ts.mean():.0f} at barriers, {tready.mean():.0f} waiting for K/V and the first stage, "
@@ -101,7 +101,7 @@ def main():
         if not os.path.exists(lib_path(name)):
             print(f"cycle_report: {lib_path(name)} is missing; run with --build first", file=sys.stderr)
             sys.exit(1)
-    runs = [("timing", "fwd"), ("timing", "dkdv"), ("timing_nosm", "fwd"), ("timing_nolds", "fwd"), ("timing_nocopy", "fwd"), ("timing_bare", "fwd")]
+    runs = [("timing", "fwd"), ("timing", "dkdv"), ("timing", "dkdv_ds"), ("timing_nosm", "fwd"), ("timing_nolds", "fwd"), ("timing_nocopy", "fwd"), ("timing_bare", "fwd")]
     for name, which in runs:
         env = dict(os.environ, IE_ATTN_LIB=lib_path(name))
         label = {"timing": "as built", "timing_nosm": "no softmax arithmetic", "timing_nolds": "no LDS reads",
