@@ -1,5 +1,6 @@
 // Measures what the bf16 matrix cores of this GPU sustain, as the denominator's reality check:
-// a register-only loop of v_mfma_f32_32x32x16_bf16 (no memory, no LDS, no VALU work), four
+// a register-only loop of v_mfma_f32_32x32x16_bf16 (and, for comparison, of the 16x16x32 shape at the same
+// FLOP per clock) with no memory, no LDS, no VALU work, four
 // independent accumulators per wave, one wave per SIMD on every CU, run for a few seconds so
 // that power management has settled.  Two operand regimes: small integers that never change
 // (little switching activity), and N(0,1)-like values cycling through 8 register sets so that
@@ -26,6 +27,7 @@
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ float pseudo_normal(unsigned& h) {  // sum of three uniforms, unit-ish variance
   float s = 0.f;
@@ -36,7 +38,7 @@ __device__ float pseudo_normal(unsigned& h) {  // sum of three uniforms, unit-is
   return (s - 1.5f) * 2.0f;
 }
 
-template <int NSET, bool RANDOM>
+template <int NSET, bool RANDOM, bool SMALL>
 __global__ __launch_bounds__(256) void mfma_loop(float* out, unsigned long long* ticks, int iters) {
   const int tid = threadIdx.x;
   const unsigned long long c0 = __builtin_readcyclecounter(), w0 = wall_clock64();
@@ -47,17 +49,30 @@ __global__ __launch_bounds__(256) void mfma_loop(float* out, unsigned long long*
       a[i][t] = RANDOM ? (__bf16)pseudo_normal(h) : (__bf16)(float)((tid * 7 + t) % 5 - 2);
       b[i][t] = RANDOM ? (__bf16)pseudo_normal(h) : (__bf16)(float)((tid + t) % 3 - 1);
     }
-  f32x16 c[4];
-  for (int i = 0; i < 4; ++i)
-    for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int u = 0; u < 16; ++u)
-      c[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u % NSET], b[(u / 4 + u) % NSET], c[u & 3], 0, 0, 0);
-  }
   float s = 0.f;
-  for (int i = 0; i < 4; ++i)
-    for (int r = 0; r < 16; ++r) s += c[i][r];
+  if constexpr (SMALL) {   // 16x16x32: half the FLOP per instruction, so two per 32x32x16
+    f32x4 c[8];
+    for (int i = 0; i < 8; ++i)
+      for (int r = 0; r < 4; ++r) c[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int u = 0; u < 32; ++u)
+        c[u & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u % NSET], b[(u / 8 + u) % NSET], c[u & 7], 0, 0, 0);
+    }
+    for (int i = 0; i < 8; ++i)
+      for (int r = 0; r < 4; ++r) s += c[i][r];
+  } else {
+    f32x16 c[4];
+    for (int i = 0; i < 4; ++i)
+      for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        c[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u % NSET], b[(u / 4 + u) % NSET], c[u & 3], 0, 0, 0);
+    }
+    for (int i = 0; i < 4; ++i)
+      for (int r = 0; r < 16; ++r) s += c[i][r];
+  }
   out[blockIdx.x * 256 + tid] = s;
   if (tid == 0) {
     ticks[2 * blockIdx.x] = __builtin_readcyclecounter() - c0;
@@ -65,7 +80,7 @@ __global__ __launch_bounds__(256) void mfma_loop(float* out, unsigned long long*
   }
 }
 
-template <int NSET, bool RANDOM>
+template <int NSET, bool RANDOM, bool SMALL = false>
 void run(float* out, unsigned long long* ticks, int cus, const char* name, double seconds) {
   const int iters = 20000;  // 16 MFMAs of 32768 FLOP per trip and wave
   hipEvent_t e0, e1;
@@ -76,7 +91,7 @@ void run(float* out, unsigned long long* ticks, int cus, const char* name, doubl
   double elapsed = 0.0;
   while (elapsed < seconds) {
     CK(hipEventRecord(e0));
-    mfma_loop<NSET, RANDOM><<<cus, 256>>>(out, ticks, iters);
+    mfma_loop<NSET, RANDOM, SMALL><<<cus, 256>>>(out, ticks, iters);
     CK(hipEventRecord(e1));
     CK(hipEventSynchronize(e1));
     CK(hipEventElapsedTime(&ms, e0, e1));
@@ -91,7 +106,7 @@ void run(float* out, unsigned long long* ticks, int cus, const char* name, doubl
   double cyc = 0, wall = 0;
   for (int i = 0; i < cus; ++i) { cyc += (double)h[2 * i]; wall += (double)h[2 * i + 1]; }
   std::free(h);
-  std::printf("%-52s %8.2f shader cycles per MFMA, shader clock %.3f GHz (last launch, mean over workgroups)\n", "",
+  std::printf("%-52s %8.2f shader cycles per 32768 FLOP of MFMA, shader clock %.3f GHz (last launch, mean over workgroups)\n", "",
               cyc / cus / ((double)iters * 16), cyc / wall * 0.1);
 }
 
@@ -106,6 +121,7 @@ int main(int argc, char** argv) {
   CK(hipMalloc(&ticks, (size_t)prop.multiProcessorCount * 16));
   run<1, false>(out, ticks, prop.multiProcessorCount, "32x32x16 bf16, constant small-integer operands", seconds);
   run<8, true>(out, ticks, prop.multiProcessorCount, "32x32x16 bf16, N(0,1) operands, 8 sets cycled", seconds);
+  run<8, true, true>(out, ticks, prop.multiProcessorCount, "16x16x32 bf16, N(0,1) operands, 8 sets cycled", seconds);
   CK(hipFree(ticks));
   CK(hipFree(out));
   return 0;
