@@ -84,3 +84,22 @@ def test_shapes_without_the_path_ignore_a_larger_workspace(S, D, causal):
     torch.cuda.synchronize()
     for a, b in zip(plain, other):
         assert torch.equal(a, b)
+
+
+def test_autograd_wrapper_with_a_shared_workspace():
+    import torch
+    from paper_2401_09149_amd import binding
+    from paper_2401_09149_amd.autograd import attention
+    dev = "cuda:0"
+    B, S, Hq, Hkv, D = 1, 768, 4, 2, 128
+    q, do = (randn_bf16((B, S, Hq, D), 791 + j).to(dev) for j in range(2))
+    k, v = (randn_bf16((B, S, Hkv, D), 793 + j).to(dev) for j in range(2))
+    scale = D ** -0.5
+    o_ref, lse_ref = binding.attn_fwd(q, k, v, scale, True, None)
+    ws = binding.alloc_bwd_workspace(q, k, None, fast=True)
+    ref = binding.attn_bwd(q, k, v, o_ref, do, lse_ref, scale, True, None, workspace=ws)
+    for _ in range(2):   # two "layers" sharing the workspace, one after the other
+        qg, kg, vg = (t.clone().requires_grad_(True) for t in (q, k, v))
+        attention(qg, kg, vg, workspace=ws).backward(do)
+        for got, want in zip((qg.grad, kg.grad, vg.grad), ref):
+            assert torch.equal(got, want)
