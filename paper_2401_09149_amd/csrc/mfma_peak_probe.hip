@@ -38,7 +38,9 @@ __device__ float pseudo_normal(unsigned& h) {  // sum of three uniforms, unit-is
   return (s - 1.5f) * 2.0f;
 }
 
-template <int NSET, bool RANDOM, bool SMALL>
+// HOLD: how many consecutive MFMAs see the same A operand (1: every MFMA gets a new A and a new B; 4: A changes
+// every fourth MFMA, as when one fragment feeds a row of output blocks; 0: A and B never change)
+template <int NSET, bool RANDOM, bool SMALL, int HOLD = 1>
 __global__ __launch_bounds__(256) void mfma_loop(float* out, unsigned long long* ticks, int iters) {
   const int tid = threadIdx.x;
   const unsigned long long c0 = __builtin_readcyclecounter(), w0 = wall_clock64();
@@ -68,7 +70,8 @@ __global__ __launch_bounds__(256) void mfma_loop(float* out, unsigned long long*
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
       for (int u = 0; u < 16; ++u)
-        c[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u % NSET], b[(u / 4 + u) % NSET], c[u & 3], 0, 0, 0);
+        c[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[HOLD == 0 ? 0 : HOLD == 1 ? u % NSET : (u / HOLD) % NSET],
+                                                           b[HOLD == 0 ? 0 : (u / 4 + u) % NSET], c[u & 3], 0, 0, 0);
     }
     for (int i = 0; i < 4; ++i)
       for (int r = 0; r < 16; ++r) s += c[i][r];
@@ -80,7 +83,7 @@ __global__ __launch_bounds__(256) void mfma_loop(float* out, unsigned long long*
   }
 }
 
-template <int NSET, bool RANDOM, bool SMALL = false>
+template <int NSET, bool RANDOM, bool SMALL = false, int HOLD = 1>
 void run(float* out, unsigned long long* ticks, int cus, const char* name, double seconds) {
   const int iters = 20000;  // 16 MFMAs of 32768 FLOP per trip and wave
   hipEvent_t e0, e1;
@@ -91,7 +94,7 @@ void run(float* out, unsigned long long* ticks, int cus, const char* name, doubl
   double elapsed = 0.0;
   while (elapsed < seconds) {
     CK(hipEventRecord(e0));
-    mfma_loop<NSET, RANDOM, SMALL><<<cus, 256>>>(out, ticks, iters);
+    mfma_loop<NSET, RANDOM, SMALL, HOLD><<<cus, 256>>>(out, ticks, iters);
     CK(hipEventRecord(e1));
     CK(hipEventSynchronize(e1));
     CK(hipEventElapsedTime(&ms, e0, e1));
@@ -121,6 +124,8 @@ int main(int argc, char** argv) {
   CK(hipMalloc(&ticks, (size_t)prop.multiProcessorCount * 16));
   run<1, false>(out, ticks, prop.multiProcessorCount, "32x32x16 bf16, constant small-integer operands", seconds);
   run<8, true>(out, ticks, prop.multiProcessorCount, "32x32x16 bf16, N(0,1) operands, 8 sets cycled", seconds);
+  run<8, true, false, 4>(out, ticks, prop.multiProcessorCount, "32x32x16 bf16, N(0,1), A held for 4 MFMAs", seconds);
+  run<8, true, false, 0>(out, ticks, prop.multiProcessorCount, "32x32x16 bf16, N(0,1), A and B never change", seconds);
   run<8, true, true>(out, ticks, prop.multiProcessorCount, "16x16x32 bf16, N(0,1) operands, 8 sets cycled", seconds);
   CK(hipFree(ticks));
   CK(hipFree(out));
