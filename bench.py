@@ -197,7 +197,7 @@ def linear_bench(iters, with_cpu, profiled_with):
            "library_ms_per_layer": lib_ms_total,
            "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(profiled_with, "linear_gemm_kernel"),
-                        "note": "all twelve products of one layer: FLOP / time; traffic: HBM bytes per launch, mean over the twelve"}}
+                        "note": "all twelve products of one layer: FLOP / time; traffic: HBM bytes per launch, mean over the three instantiations' means"}}
     if with_cpu:
         import numpy as np
         from oracle import linear as ora
@@ -286,6 +286,19 @@ def main():
     dkdv_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DKDV), it)
     dq_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DQ), it)   # (with a stored dS: reads what the dK/dV phase just left)
 
+    # the other backward path (small workspace: dQ recomputes S, P, dP), for comparison; not part of `value`
+    other = None
+    if stored_ds:
+        ws_small = binding.alloc_bwd_workspace(q, k, cu)
+        bwd_small = lambda ph=binding.BWD_ALL: binding.ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu, cfg.scale,
+                                                                          cfg.causal, ws_small, ph)
+        bwd_small()
+        o_ms, _, _ = event_ms(bwd_small, it)
+        o_dq, _, _ = event_ms(lambda: bwd_small(binding.BWD_DQ), it)
+        o_dkdv, _, _ = event_ms(lambda: bwd_small(binding.BWD_DKDV), it)
+        other = {"path": "recompute", "ms": o_ms, "dq_ms": o_dq, "dkdv_ms": o_dkdv, "workspace_bytes": ws_small.numel()}
+        del ws_small
+
     f_fwd = W.fwd_flops(cfg, cu_np)
     f_bwd = W.bwd_flops(cfg, cu_np)
     value = (f_fwd + f_bwd) / (ms_per_step * 1e-3) / 1e12
@@ -301,7 +314,7 @@ def main():
     pairs = f_fwd / (4.0 * cfg.D)   # = B * Hq * sum L^2 / 2
     kernels = {
         ("attn_fwd_wide_kernel" if cfg.D == 128 else "attn_fwd_kernel"): (fwd_ms, 4.0 * cfg.D * pairs),
-        "attn_bwd_dkdv_kernel": (dkdv_ms, 8.0 * cfg.D * pairs),
+        ("attn_bwd_dkdv_kernel_store_ds" if stored_ds else "attn_bwd_dkdv_kernel"): (dkdv_ms, 8.0 * cfg.D * pairs),
     }
     if stored_ds:
         kernels["attn_bwd_dq_from_ds_kernel"] = (dq_ms, float(cfg.B) * cfg.Hq * cfg.S * (cfg.S + 128))   # bytes
@@ -337,7 +350,7 @@ def main():
         "fwd": {"ms": fwd_ms, "ms_min": fwd_min, "ms_median": fwd_med, "tflops": fwd_tflops, "frac_of_peak": fwd_tflops / PEAK_BF16_TFLOPS},
         "bwd": {"ms": bwd_ms, "ms_min": bwd_min, "ms_median": bwd_med, "tflops": bwd_tflops, "frac_of_peak": bwd_tflops / PEAK_BF16_TFLOPS,
                 "delta_ms": delta_ms, "dq_ms": dq_ms, "dkdv_ms": dkdv_ms,
-                "path": "stored_ds" if stored_ds else "recompute", "workspace_bytes": ws.numel()},
+                "path": "stored_ds" if stored_ds else "recompute", "workspace_bytes": ws.numel(), "other_path": other},
         "peak_tflops": PEAK_BF16_TFLOPS,
         "fwd_tile_efficiency": tile_efficiency(cfg, cu_np) if cfg.D == 128 else tile_efficiency(cfg, cu_np, 128, 64),
         "roofline": roofline,

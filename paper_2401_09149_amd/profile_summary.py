@@ -76,12 +76,19 @@ def traffic(fetch_csv, write_csv, out, workload, command):
     sw = kib / cw if cw else 1.0
     res = {"workload": workload, "command": command, "fetch_scale": sf, "write_scale": sw,
            "copy_fetch_counter": cf, "copy_write_counter": cw, "bytes_per_launch": {}, "detail": {}}
+    groups = collections.defaultdict(list)   # instantiations of one kernel template share a name: mean over them
     for k in fetch:
         if not ours(k):
             continue
         fb = fetch[k].get("FETCH_SIZE", 0.0) * sf * 1024.0
         wb = write.get(k, {}).get("WRITE_SIZE", 0.0) * sw * 1024.0
         name = k.split("<")[0]
+        if name == "attn_bwd_dkdv_kernel" and "true" in k:   # except the instantiation that also stores dS
+            name += "_store_ds"
+        groups[name].append((fb, wb))
+    for name, vals in groups.items():
+        fb = sum(v[0] for v in vals) / len(vals)
+        wb = sum(v[1] for v in vals) / len(vals)
         res["bytes_per_launch"][name] = fb + wb
         res["detail"][name] = {"fetch_bytes": fb, "write_bytes": wb}
     with open(out, "w") as f:
