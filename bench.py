@@ -191,10 +191,21 @@ def linear_bench(iters, with_cpu, profiled_with):
         ms_total += sum(ours)
         lib_ms_total += sum(lib)
         del x, w, dy, y, dx, dw
+    # the 65B gate/up projection whose output is the (16384, 22016) activation of the appendix on memory fragmentation
+    M2, N2, K2 = 16384, 22016, 8192
+    x, w, dy = mk(M2, K2), mk(N2, K2), mk(M2, N2)
+    y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+    ours = [timed(lambda: binding.ie_linear_fwd(x, w, y)), timed(lambda: binding.ie_linear_bwd_input(dy, w, dx)),
+            timed(lambda: binding.ie_linear_bwd_weight(dy, x, dw))]
+    lib = [timed(lambda: torch.matmul(x, w.t(), out=y)), timed(lambda: torch.matmul(dy, w, out=dx)),
+           timed(lambda: torch.matmul(dy.t(), x, out=dw))]
+    flop2 = 2.0 * M2 * N2 * K2
+    big = {"M": M2, "N": N2, "K": K2, "tflops": [flop2 / t / 1e9 for t in ours], "library_tflops": [flop2 / t / 1e9 for t in lib]}
+    del x, w, dy, y, dx, dw
     achieved = flop_total / ms_total / 1e9
     out = {"workload": "7b_linear_m8192", "M": M, "dtype": "bf16", "kernel": "linear_gemm_kernel",
            "order": ["fwd", "bwd_input", "bwd_weight"], "per_module": per, "ms_per_layer": ms_total,
-           "library_ms_per_layer": lib_ms_total,
+           "library_ms_per_layer": lib_ms_total, "gate_up_65b_m16384": big,
            "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(profiled_with, "linear_gemm_kernel"),
                         "note": "all twelve products of one layer: FLOP / time; traffic: HBM bytes per launch, mean over the three instantiations' means"}}

@@ -76,10 +76,11 @@ def test_output_columns_that_are_multiples_of_8_only():
     run_all(128, 128, 200, seed=8, which=("dx", "dw"))   # dx and dw rows of 200
 
 
-def test_paper_shapes_sampled():
-    """7B attention-block projections at one GPU's 8192 tokens (hidden 4096): whole outputs against the oracle
-    would take minutes of float64 matmul, so 64 sampled rows of each output are compared."""
-    M, N, K = 8192, 12288, 4096
+@pytest.mark.parametrize("M,N,K", [(8192, 12288, 4096), (16384, 22016, 8192)])
+def test_paper_shapes_sampled(M, N, K):
+    """7B QKV projection at one GPU's 8192 tokens (hidden 4096), and the 65B gate/up projection whose output is the
+    (16384, 22016) activation of the appendix on memory fragmentation (hidden 8192; Table 1): whole outputs against
+    the oracle would take minutes of float64 matmul, so 64 sampled rows of each output are compared."""
     x, w, dy = randn_bf16((M, K), 21), randn_bf16((N, K), 22), randn_bf16((M, N), 23)
     xd, wd, dyd = x.to(DEV), w.to(DEV), dy.to(DEV)
     y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
