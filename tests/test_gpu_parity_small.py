@@ -213,6 +213,13 @@ def test_autograd_wrapper_gives_the_same_gradients():
     o.backward(do)
     for got, want in zip((qg.grad, kg.grad, vg.grad), ref):
         assert torch.equal(got, want)
+    # activation recomputation: the backward pass runs the forward kernel again; same bits
+    qr, kr, vr = (t.clone().requires_grad_(True) for t in (q, k, v))
+    o2 = attention(qr, kr, vr, recompute=True)
+    assert torch.equal(o2, o_ref)
+    o2.backward(do)
+    for got, want in zip((qr.grad, kr.grad, vr.grad), ref):
+        assert torch.equal(got, want)
 
 
 def test_error_codes_on_device_tensors():
