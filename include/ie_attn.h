@@ -28,6 +28,9 @@
  *     stream) and the buffers must stay alive until the stream has passed it.
  *     Calls may overlap on different streams; each launch takes the next of 256 counter slots, so
  *     more than 256 launches of one kernel in flight at once would share one.
+ *     A call enqueues kernel launches only (no memset, no copy, no allocation), so it may be recorded
+ *     under stream capture; the counter slot is then fixed in the graph, and two replays of the same
+ *     graph must not run at the same time.
  *   - q, o, dout, dq : contiguous [B, S, Hq,  D] bf16.
  *     k, v, dk, dv   : contiguous [B, S, Hkv, D] bf16.
  *     lse            : contiguous [B, Hq, S] fp32, natural log, `scale` included.

@@ -229,3 +229,42 @@ def test_error_codes_on_device_tensors():
     with pytest.raises(binding.IeAttnError) as e:
         binding.attn_fwd(q, q, q, 0.1)
     assert e.value.code == -3
+
+
+def test_forward_and_backward_can_be_captured_in_a_graph_and_replayed():
+    """The library only launches kernels on the caller's stream (no allocation, no memset, no synchronisation), so a
+    step can be captured into a graph.  Replays, with eager work and synchronisation between them and with new input
+    values each time, must give the bits of the eager calls; both backward paths."""
+    import torch
+    from paper_2401_09149_amd import binding
+    dev = "cuda:0"
+    B, S, Hq, Hkv, D = 1, 1024, 4, 2, 128
+    scale = D ** -0.5
+    q, do = (randn_bf16((B, S, Hq, D), 901 + j).to(dev) for j in range(2))
+    k, v = (randn_bf16((B, S, Hkv, D), 903 + j).to(dev) for j in range(2))
+    o = torch.empty_like(q)
+    lse = torch.empty((B, Hq, S), dtype=torch.float32, device=dev)
+    for fast in (False, True):
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws = binding.alloc_bwd_workspace(q, k, None, fast=fast)
+
+        def step():
+            binding.ie_attn_fwd(q, k, v, o, lse, None, scale, True)
+            binding.ie_attn_bwd(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws)
+
+        step()   # eager once: one-time set-up (occupancy queries) happens outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for trial in range(3):
+            q.copy_(randn_bf16((B, S, Hq, D), 910 + trial).to(dev))   # new values in the captured buffers
+            step()
+            torch.cuda.synchronize()
+            want = [t.clone() for t in (o, lse, dq, dk, dv)]
+            for t in (o, lse, dq, dk, dv):
+                t.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            for got, ref in zip((o, lse, dq, dk, dv), want):
+                assert torch.equal(got, ref), (fast, trial)
