@@ -364,10 +364,10 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   // dS workspace (STORE_DS): this lane's 32-byte slot inside the block of the step's (query head, query
   // tile), for 32-query block 0 (block rb adds 2048); the block itself is located once per step (ds_step)
   const uint32_t ds_lane = (uint32_t)(k0 / 32 + wv) * 8192u + (uint32_t)h * 1024u + (uint32_t)((n ^ (h << 2)) << 5);
-  // (dense input, S a multiple of 128: query tile it = k0 / BK + tile_idx; consecutive blocks of a head are
-  // 32768 (it + 1) bytes apart, heads ds_head bytes)
-  const int64_t ds_head = STORE_DS ? ds_matrix_offset(p.S / BQ, 1, 0) : 0;
-  char* ds_first = STORE_DS ? reinterpret_cast<char*>(p.ds) + ds_matrix_offset(p.S / BQ, (int64_t)tc.b * p.Hq + g * group, k0 / BK)
+  // (dense input, S a multiple of 128: the step's query tile is it0 + tile_idx)
+  const int it0 = (int)((q_begin - tc.doc_begin) / BQ);
+  const int64_t ds_head = STORE_DS ? ds_matrix_offset(p.S / BQ, 1, 0, p.causal != 0) : 0;
+  char* ds_first = STORE_DS ? reinterpret_cast<char*>(p.ds) + ds_matrix_offset(p.S / BQ, (int64_t)tc.b * p.Hq + g * group, it0, p.causal != 0)
                             : nullptr;   // first step of the current query head
   char* ds_step = ds_first;
   bf16x8 kf[NKS], vf[NKS];                   // live in AGPRs
@@ -707,7 +707,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 #endif
     if (STORE_DS) {
       if (next_tile == 0) { ds_first += ds_head; ds_step = ds_first; }
-      else ds_step += (int64_t)((int)(k0 / BK) + next_tile) * 32768;
+      else ds_step += ds_matrix_bytes(p.S / BQ, it0 + tile_idx, p.causal != 0);
     }
     hq_idx = next_hq;
     tile_idx = next_tile;
@@ -786,14 +786,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
   const int64_t q0 = tc.t0;
   const int ita = (int)(q0 / 128);                // first tile; the second is ita + 1 unless S ends before it
   const bool has_b = q0 + 128 < p.S;
-  const int nkt_a = (ita + 1) * (128 / BN);       // stages the first tile takes part in
-  const int nkt = has_b ? nkt_a + 128 / BN : nkt_a;
+  const bool causal = p.causal != 0;
+  const int nkt_a = causal ? (ita + 1) * (128 / BN) : (int)(p.S / BN);   // stages the first tile takes part in
+  const int nkt = has_b && causal ? nkt_a + 128 / BN : nkt_a;
 
   const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
   const char* kbase = reinterpret_cast<const char*>(p.k + ((int64_t)tc.b * p.S * p.Hkv + g) * D);
   const int64_t bh = (int64_t)tc.b * p.Hq + tc.h;
-  const char* sa = reinterpret_cast<const char*>(p.ds) + ds_matrix_offset(p.S / 128, bh, ita);
-  const char* sb = has_b ? sa + (int64_t)(ita + 1) * 32768 : sa;   // (without a second tile: valid memory, never used)
+  const char* sa = reinterpret_cast<const char*>(p.ds) + ds_matrix_offset(p.S / 128, bh, ita, causal);
+  const char* sb = has_b ? sa + ds_matrix_bytes(p.S / 128, ita, causal) : sa;   // (without a second tile: valid memory, never used)
 
   const uint32_t lds0 = lds_address(smem);
   AsyncTile<D> ldk;

@@ -50,17 +50,20 @@ struct AttnParams {
   __bf16* ds;               // optional workspace: dS written by the dK/dV kernel for the dQ kernel (see ds_matrix_offset), or NULL
 };
 
-// Layout of the dS workspace (dense causal input, S a multiple of 128, head dimension 128): for every
-// (batch b, query head hq, 128-query tile it) the elements dS[query][key] of the tile's queries and keys
-// 0 .. 128 (it + 1), bf16, 256 bytes per key; the blocks of one head follow each other by it, heads by (b, hq).
+// Layout of the dS workspace (dense input, S a multiple of 128, head dimension 128): for every
+// (batch b, query head hq, 128-query tile it) the elements dS[query][key] of the tile's queries and the keys they
+// can see (causal: keys 0 .. 128 (it + 1); otherwise all S), bf16, 256 bytes per key; the blocks of one head follow
+// each other by it, heads by (b, hq).
 // Inside a block the order is the one in which the dK/dV kernel holds dS in registers, so that a wavefront stores
 // 2 KiB contiguous: [32-key group][32-query block rb][half-wave hh][key n of the group, at slot n ^ 4 hh]
 // [16 values e], where value e belongs to query 32 rb + 8 (e / 4) + 4 hh + e % 4 (register e of the score
 // block's C layout).  The dQ kernel copies 32-key groups (8 KiB) into LDS as they are; the exchange of slots
 // n and n ^ 4 for hh = 1 spreads its transpose loads over the banks.
-__host__ __device__ inline int64_t ds_matrix_offset(int64_t nt, int64_t bh, int64_t it) {   // in bytes
-  return (bh * (nt * (nt + 1) / 2) + it * (it + 1) / 2) * 32768;
+__host__ __device__ inline int64_t ds_matrix_offset(int64_t nt, int64_t bh, int64_t it, bool causal) {   // in bytes
+  return causal ? (bh * (nt * (nt + 1) / 2) + it * (it + 1) / 2) * 32768 : (bh * nt + it) * nt * 32768;
 }
+// Bytes between the blocks of query tiles it and it + 1 of one head.
+__host__ __device__ inline int64_t ds_matrix_bytes(int64_t nt, int64_t it, bool causal) { return (causal ? it + 1 : nt) * 32768; }
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);

@@ -80,19 +80,19 @@ size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv
   return 2 * align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256);  // delta and lse*log2e, [B,Hq,S] each
 }
 
-// dS of causal dense input: per (batch, query head) the lower block triangle of 128 x 128 blocks, bf16.
-static size_t ds_bytes(int64_t B, int64_t S, int32_t Hq) {
+// dS of dense input, bf16 in 128 x 128 blocks: per (batch, query head) the lower block triangle when causal, else all.
+static size_t ds_bytes(int64_t B, int64_t S, int32_t Hq, int32_t causal) {
   const size_t nt = (size_t)(S / 128);
-  return (size_t)B * (size_t)Hq * (nt * (nt + 1) / 2) * 32768;
+  return (size_t)B * (size_t)Hq * (causal ? nt * (nt + 1) / 2 : nt * nt) * 32768;
 }
 
 size_t ie_attn_bwd_fast_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs,
                                         int32_t causal) {
   const size_t base = ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs);
-  if (base == 0 || num_docs != 0 || causal != 1 || D != 128 || S % 128 != 0) return base;
+  if (base == 0 || num_docs != 0 || (causal != 0 && causal != 1) || D != 128 || S % 128 != 0) return base;
   // (the kernels keep byte offsets inside one query tile's block in 32 bits: 256 S bytes; and no device holds 2^50)
   if (S >= ((int64_t)1 << 23) || (double)B * Hq * (double)S * ((double)S + 128) > 1e15) return base;
-  return base + ds_bytes(B, S, Hq);
+  return base + ds_bytes(B, S, Hq, causal);
 }
 
 int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,

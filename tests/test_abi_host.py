@@ -54,12 +54,12 @@ def test_workspace_query(lib):
 
 
 def test_fast_workspace_query(lib):
-    """Room for dS only where the dS-storing backward path exists: dense, causal, D = 128, S % 128 == 0."""
+    """Room for dS only where the dS-storing backward path exists: dense, D = 128, S % 128 == 0."""
     base, fast = lib.ie_attn_bwd_workspace_bytes, lib.ie_attn_bwd_fast_workspace_bytes
     assert fast(1, 32768, 32, 32, 128, 0, 1) == base(1, 32768, 32, 32, 128, 0) + 32 * 32768 * (32768 + 128)
     assert fast(2, 256, 8, 2, 128, 0, 1) == base(2, 256, 8, 2, 128, 0) + 2 * 8 * 256 * 384
-    for args in ((1, 32768, 32, 32, 128, 0, 0),      # not causal
-                 (1, 32768, 32, 32, 64, 0, 1),       # head dimension 64
+    assert fast(1, 4096, 8, 8, 128, 0, 0) == base(1, 4096, 8, 8, 128, 0) + 2 * 8 * 4096 * 4096   # not causal: all blocks
+    for args in ((1, 32768, 32, 32, 64, 0, 1),       # head dimension 64
                  (1, 32768 + 64, 32, 32, 128, 0, 1), # ragged
                  (1, 32768, 32, 32, 128, 5, 1),      # packed documents
                  (1, 1 << 23, 1, 1, 128, 0, 1)):     # beyond the 32-bit offsets inside a block
