@@ -8,6 +8,8 @@
 //                    dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T
 //   attn_bwd_dkdv  : key-stationary: S = Q K^T, dP = dO V^T, dV^T += dO^T P,
 //                    dK^T += Q^T dS, looping over the query heads of the kv head's group
+// When the caller's workspace has room for it, the dK/dV kernel also stores dS and dQ comes from
+//   attn_bwd_dq_from_ds : dQ^T += K^T dS^T, a stream over the stored dS (five products in all instead of seven)
 // In both main kernels the elementwise results leave the first products in the C layout
 // (one column per lane, rows over registers) with the NEXT contraction index on the
 // rows, so they feed the following MFMA from registers; the transposed operands
