@@ -160,6 +160,44 @@ class AnalyticCompute:
         return fwd * (1 + plan.a) + bwd
 
 
+class ProfiledCompute(AnalyticCompute):
+    """UPro with a measured attention table (Sec. 4.2: self-atten(b, S, H, D / s_sp) is profiled on one GPU and the
+    simulator looks the times up): `table` is the JSON that `self_atten_sweep --json` writes.  A shape that was
+    measured is looked up; any other falls back to the measured shape with the nearest FLOP count, scaled by the ratio
+    of FLOP counts (attention time is proportional to b * heads * S^2 once the chip is full).  The linear modules stay
+    analytic.  `stored_ds`: use the backward time of the path that stores dS where the table has one."""
+
+    def __init__(self, table, linear_flops=1.15e15, stored_ds=True):
+        super().__init__(linear_flops=linear_flops)
+        import json
+        if isinstance(table, str):
+            with open(table) as f:
+                table = json.load(f)
+        self.records = {}
+        for r in table["records"]:
+            bwd = r["bwd_stored_ds_ms"] if stored_ds and r.get("bwd_stored_ds_ms") else r["bwd_ms"]
+            self.records[(r["b"], r["S"], r["heads"])] = (r["fwd_ms"] * 1e-3, bwd * 1e-3)
+        if not self.records:
+            raise ValueError("empty attention table")
+
+    def attention_times(self, b, S, heads):
+        """(forward, backward) seconds of self-atten(b, S, heads) on one GPU."""
+        hit = self.records.get((b, S, heads))
+        if hit:
+            return hit
+        want = float(b) * heads * S * S
+        key = min(self.records, key=lambda k: abs(math.log(want / (float(k[0]) * k[2] * k[1] * k[1]))))
+        f, bw_ = self.records[key]
+        ratio = want / (float(key[0]) * key[2] * key[1] * key[1])
+        return f * ratio, bw_ * ratio
+
+    def layer_time(self, model, plan, S):
+        g = max(plan.s_sp, plan.s_tp)
+        lin_fwd = 2.0 * plan.b * S * model.psi / g / self.linear
+        a_fwd, a_bwd = self.attention_times(plan.b, S, max(1, model.heads // g))
+        return (a_fwd + lin_fwd) * (1 + plan.a) + a_bwd + 2.0 * lin_fwd
+
+
 def step_time(plan, model, S, N, bw, compute, R=1.3, t_other=0.0):
     """T_fwd_bwd + T_update (Sec. 4.5).  The sharding traffic of the optimizer step is T_update; everything else
     overlaps with computation at the cost of the slowdown R (OPro, Sec. 4.2)."""

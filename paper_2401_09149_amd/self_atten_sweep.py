@@ -8,7 +8,10 @@ rounded to bf16, drawn on the device (timing only; parity is the tests' business
 timed twice: with the small workspace (dQ recomputes S, P, dP) and, where B*Hq*S*(S+128) bytes more fit the
 limit given by --ds-limit-gb, with the workspace that lets the dK/dV kernel store dS.
 
-    python -m paper_2401_09149_amd.self_atten_sweep [--iters 5] [--out profiles/self_atten_sweep.md]
+    python -m paper_2401_09149_amd.self_atten_sweep [--iters 5] [--out profiles/self_atten_sweep.md] [--json table.json]
+
+The JSON table (one record per shape: b, S, heads, head_dim, fwd_ms, bwd_ms, bwd_stored_ds_ms) is what
+planner.ProfiledCompute reads in place of its analytic attention rate.
 """
 import argparse
 import sys
@@ -35,6 +38,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=5)
     ap.add_argument("--out", default=None, help="also write the table (markdown) to this file")
+    ap.add_argument("--json", default=None, help="also write the measurements as a JSON table for planner.ProfiledCompute")
     ap.add_argument("--ds-limit-gb", type=float, default=160.0, help="largest workspace for the stored-dS backward path")
     args = ap.parse_args()
     import torch
@@ -50,6 +54,7 @@ def main():
     scale = D ** -0.5
     lines = ["| model | S | b | s_sp | heads/GPU | fwd ms | fwd TFLOP/s | bwd ms | bwd TFLOP/s | bwd ms, stored dS | workspace GB | fwd+bwd % of 2.5 PFLOP/s (faster bwd) |",
              "|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    records = []
     for model, S, b, s_sp, H in shapes():
         mk = lambda: torch.randn((b, S, H, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
         q, k, v, do = mk(), mk(), mk(), mk()
@@ -86,7 +91,14 @@ def main():
                 f"{100 * both / PEAK_BF16_TFLOPS:.1f} |")
         print(line, flush=True)
         lines.append(line)
+        records.append({"model": model, "b": b, "S": S, "s_sp": s_sp, "heads": H, "head_dim": D, "fwd_ms": f_ms, "bwd_ms": b_ms,
+                        "bwd_stored_ds_ms": s_ms, "stored_ds_workspace_bytes": big if s_ms is not None else None})
         del q, k, v, do, o, lse, dq, dk, dv, ws
+    if args.json:
+        import json
+        with open(args.json, "w") as f:
+            json.dump({"kernel": "ie_attn_fwd / ie_attn_bwd, causal, bf16", "iters": args.iters, "records": records}, f, indent=1)
+            f.write("\n")
     if args.out:
         with open(args.out, "w") as f:
             f.write("# self-atten(b, S, H, D/s_sp) on one MI355X over the paper's own plans (Appendix Tables 4-7, \"Our Work\")\n\n")

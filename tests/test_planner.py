@@ -157,3 +157,27 @@ def test_measured_layer_time_on_the_gpu_is_close_to_the_analytic_stand_in():
     analytic = pl.AnalyticCompute().layer_time(m, plan, S)
     print(f"measured {measured * 1e3:.2f} ms, analytic {analytic * 1e3:.2f} ms", flush=True)
     assert 0.6 * analytic < measured < 1.6 * analytic
+
+
+def test_profiled_compute_looks_up_and_scales():
+    """A measured table replaces the analytic attention rate: exact shapes are looked up, others scale by
+    b * heads * S^2 from the nearest measured shape, and the linear part stays analytic."""
+    table = {"records": [
+        {"b": 1, "S": 32768, "heads": 8, "fwd_ms": 2.0, "bwd_ms": 6.0, "bwd_stored_ds_ms": 5.0},
+        {"b": 1, "S": 65536, "heads": 4, "fwd_ms": 4.0, "bwd_ms": 12.0, "bwd_stored_ds_ms": None},
+    ]}
+    pc = pl.ProfiledCompute(table)
+    assert pc.attention_times(1, 32768, 8) == (2.0e-3, 5.0e-3)
+    assert pl.ProfiledCompute(table, stored_ds=False).attention_times(1, 32768, 8) == (2.0e-3, 6.0e-3)
+    assert pc.attention_times(1, 65536, 4) == (4.0e-3, 12.0e-3)          # no stored-dS time: the recomputing one
+    f, b = pc.attention_times(1, 32768, 10)                               # 1.25 times the work of the first record
+    assert abs(f - 2.5e-3) < 1e-12 and abs(b - 6.25e-3) < 1e-12
+    m = pl.MODELS["7B"]
+    plan = pl.Plan(b=1, n=1, a=0, s_pp=1, s_dp=1, s_tp=1, s_sp=4, s_ps=1, s_gs=1, s_oss=1)
+    lin = 2.0 * 32768 * m.psi / 4 / pc.linear
+    assert abs(pc.layer_time(m, plan, 32768) - (2.0e-3 + 5.0e-3 + 3 * lin)) < 1e-12
+    plan_a = pl.Plan(b=1, n=1, a=1, s_pp=1, s_dp=1, s_tp=1, s_sp=4, s_ps=1, s_gs=1, s_oss=1)
+    assert abs(pc.layer_time(m, plan_a, 32768) - (2 * (2.0e-3 + lin) + 5.0e-3 + 2 * lin)) < 1e-12
+    # usable by the search in place of the analytic model
+    best = pl.search(m, 32768, 32, 4 * 2 ** 20, 80e9, compute=pc, top=3)
+    assert best and all(t > 0 for t, _ in best)
