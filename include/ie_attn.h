@@ -88,7 +88,7 @@ size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv
  * D == 128 and S a multiple of 128 this is ie_attn_bwd_workspace_bytes(...) plus room for dS = P o (dP - delta) in
  * bf16: B * Hq * S * (S + 128) bytes when causal (the lower block triangle of every head), 2 * B * Hq * S * S otherwise.
  * Given that much, the dK/dV kernel stores the dS it forms and dQ = scale * dS K is computed from it, instead of
- * recomputing S, P and dP a second time for dQ (seven matrix products per block pair instead of nine; Sec. 4.3 counts
+ * recomputing S, P and dP a second time for dQ (five matrix products per block pair instead of seven; Sec. 4.3 counts
  * the backward pass as the compute-heavier direction).  The results differ from the recomputing path only in
  * summation order (same bf16 dS, fp32 accumulation).  For every other shape the function returns
  * ie_attn_bwd_workspace_bytes(...): there is no such path and a larger workspace changes nothing.  Pure host arithmetic.
