@@ -231,7 +231,7 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the workload table (default: the headline config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-prefix", type=int, default=32768)
-    ap.add_argument("--cpu-heads", type=int, default=2)
+    ap.add_argument("--cpu-heads", type=int, default=1)
     ap.add_argument("--sp-config", type=int, default=1, help="index into the re-layout workload table; -1 skips that part")
     ap.add_argument("--no-linear", action="store_true", help="skip the linear-module part")
     ap.add_argument("--recompute-ds", action="store_true",
