@@ -152,7 +152,7 @@ def sp_permute_bench(cfg, iters, with_cpu, profiled_with):
 
 
 def linear_bench(iters, with_cpu, profiled_with):
-    """The linear modules of one 7B layer (hidden 4096, MLP 11008; Table 1) applied to one GPU's 8192 tokens of the
+    """The linear modules of one 7B layer (hidden 4096, MLP 11008; Table 2) applied to one GPU's 8192 tokens of the
     paper's 32K plan (s_sp = 4): forward, input gradient and weight gradient of the QKV, output, gate/up and down
     projections.  FLOP = 2 M N K per product.  torch.matmul (the vendor library) on the same operands is timed
     beside it as context."""

@@ -4,10 +4,10 @@
  *
  * This is the per-GPU step of hybrid sequence parallelism: after the first all-to-all
  * every GPU holds Q, K and V of all S tokens for heads/s_sp heads, laid out
- * [B, S, heads_local, head_dim] (Sec. 2.2 "SP-2", Sec. 3.1 "Sequence Parallelism"), and
+ * [B, S, heads_local, head_dim] (Sec. 2.4 "SP-2", Sec. 3.2.2 "Sequence Parallelism"), and
  * runs fused multi-head attention on them (Sec. 2.1 "Transformer Architecture";
  * Sec. 4.2 "Computation Profiler": self-atten(b, S, H, D/s_sp) on a single GPU).  The
- * backward pass recomputes the probabilities instead of storing them (Sec. 3.1: the
+ * backward pass recomputes the probabilities instead of storing them (Sec. 3.2: the
  * fused kernel includes selective activation recomputation), so only o and the
  * per-row log-sum-exp travel from forward to backward.
  *
@@ -88,7 +88,7 @@ size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv
  * D == 128 and S a multiple of 128 this is ie_attn_bwd_workspace_bytes(...) plus room for dS = P o (dP - delta) in
  * bf16: B * Hq * S * (S + 128) bytes when causal (the lower block triangle of every head), 2 * B * Hq * S * S otherwise.
  * Given that much, the dK/dV kernel stores the dS it forms and dQ = scale * dS K is computed from it, instead of
- * recomputing S, P and dP a second time for dQ (five matrix products per block pair instead of seven; Sec. 4.3 counts
+ * recomputing S, P and dP a second time for dQ (five matrix products per block pair instead of seven; the appendix "Implementation Detail: Selective Overlap" counts
  * the backward pass as the compute-heavier direction).  The results differ from the recomputing path only in
  * summation order (same bf16 dS, fp32 accumulation).  For every other shape the function returns
  * ie_attn_bwd_workspace_bytes(...): there is no such path and a larger workspace changes nothing.  Pure host arithmetic.
@@ -99,8 +99,8 @@ size_t ie_attn_bwd_fast_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_
 /*
  * Backward: given dout and the forward's o and lse, writes dq, dk, dv (fully
  * overwritten; dk/dv are summed over the Hq/Hkv query heads of each kv head).  The
- * probabilities are recomputed from lse (Sec. 3.1), backward costs 2.5x the forward's
- * matrix work (cf. Sec. 4.3: backward is about twice as compute-intensive as forward).
+ * probabilities are recomputed from lse (Sec. 3.2), backward costs 2.5x the forward's
+ * matrix work (cf. the appendix "Implementation Detail: Selective Overlap": backward is about twice as compute-intensive as forward).
  * `workspace` is caller-owned scratch of at least ie_attn_bwd_workspace_bytes(...) bytes,
  * 256-byte aligned; its contents after the call are unspecified.  With at least
  * ie_attn_bwd_fast_workspace_bytes(...) bytes the dS-storing path described there is taken.  Every output element

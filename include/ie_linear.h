@@ -4,7 +4,7 @@
  *
  * Next to self-attention the linear modules are the main contributors to a layer's computation time, and
  * under sequence parallelism without tensor parallelism each GPU applies them to its (b, S/s_sp, H) slice
- * of the input with the complete weight matrices (Sec. 2.2 "SP-2"; Sec. 4.2 "Computation Profiler").  With
+ * of the input with the complete weight matrices (Sec. 2.4 "SP-2"; Sec. 4.2 "Computation Profiler").  With
  * M = b * S/s_sp tokens, weight w [N, K] (N outputs, K inputs, as stored by the framework):
  *     forward          y  = x w^T        x  [M, K] -> y  [M, N]
  *     backward, input  dx = dy w         dy [M, N] -> dx [M, K]
@@ -35,7 +35,7 @@ int ie_linear_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N, i
 /* dx[M,K] = dy[M,N] w[N,K]: gradient with respect to the module's input. */
 int ie_linear_bwd_input(const void* dy, const void* w, void* dx, int64_t M, int64_t N, int64_t K, void* stream);
 
-/* dw[N,K] = dy[M,N]^T x[M,K]: gradient with respect to the weight (Sec. 4.3: backward costs about twice the
+/* dw[N,K] = dy[M,N]^T x[M,K]: gradient with respect to the weight (the appendix "Implementation Detail: Selective Overlap": backward costs about twice the
  * forward: two products instead of one). */
 int ie_linear_bwd_weight(const void* dy, const void* x, void* dw, int64_t M, int64_t N, int64_t K, void* stream);
 

@@ -4,7 +4,7 @@
  * With sequence parallelism of degree P = s_sp and no tensor parallelism, every module except
  * attention works on a slice of S/P tokens with all heads, and attention works on all S tokens
  * with heads/P heads; an all-to-all before attention and one after it change between the two
- * partitions (Sec. 2.2 "SP-2"; Sec. 3.1 "Sequence Parallelism": 6bSH bytes in the first
+ * partitions (Sec. 2.4 "SP-2"; Sec. 3.2.2 "Sequence Parallelism": 6bSH bytes in the first
  * exchange, 2bSH in the second, per layer and direction).  An all-to-all moves P equal,
  * contiguous chunks, chunk p to and from peer p; the tensors on either side are not laid out that
  * way, so each exchange has a local permutation before it ("pack") and one after it ("unpack").
@@ -19,7 +19,7 @@
  * Layouts (all contiguous, bf16; "|" is concatenation):
  *   qkv_local  [B][ q:[Sl][Hq][D] | k:[Sl][Hkv][D] | v:[Sl][Hkv][D] ]
  *              the fused QKV projection of this GPU's sequence slice; with Hq == Hkv this is the
- *              B x 3 x S/s_sp x H tensor of Sec. 2.2.
+ *              B x 3 x S/s_sp x H tensor of Sec. 2.4.
  *   xqkv       [P][B][ q:[Sl][Hql][D] | k:[Sl][Hkvl][D] | v:[Sl][Hkvl][D] ]
  *              exchange buffer of the first all-to-all.  Sent: chunk p = head group p of this
  *              GPU's sequence slice.  Received: chunk p = sequence slice p of this GPU's head group.
@@ -50,17 +50,17 @@
 extern "C" {
 #endif
 
-/* Forward, before the first all-to-all (Sec. 2.2 "SP-2": the output of Linear_qkv is exchanged):
+/* Forward, before the first all-to-all (Sec. 2.4 "SP-2": the output of Linear_qkv is exchanged):
  * xqkv[p][b][t][s][hl][:] = qkv_local[b][t][s][p*Hl_t + hl][:], t in {q, k, v}. */
 int ie_sp_pack_qkv(const void* qkv_local, void* xqkv, int64_t B, int64_t Sl, int32_t Hq, int32_t Hkv, int32_t D,
                    int32_t P, void* stream);
 
-/* Forward, after the first all-to-all (Sec. 2.2: every GPU then holds the complete sequence of Q, K
+/* Forward, after the first all-to-all (Sec. 2.4: every GPU then holds the complete sequence of Q, K
  * and V for a subset of the heads): t[b][p*Sl + s][hl][:] = xqkv[p][b][t][s][hl][:]. */
 int ie_sp_unpack_qkv(const void* xqkv, void* q, void* k, void* v, int64_t B, int64_t Sl, int32_t Hq, int32_t Hkv,
                      int32_t D, int32_t P, void* stream);
 
-/* Forward, before the second all-to-all (Sec. 2.2: the attention results are gathered and
+/* Forward, before the second all-to-all (Sec. 2.4: the attention results are gathered and
  * re-partitioned along the sequence): xo[p][b][s][hl][:] = o[b][p*Sl + s][hl][:]. */
 int ie_sp_pack_o(const void* o, void* xo, int64_t B, int64_t Sl, int32_t Hq, int32_t D, int32_t P, void* stream);
 
@@ -68,7 +68,7 @@ int ie_sp_pack_o(const void* o, void* xo, int64_t B, int64_t Sl, int32_t Hq, int
 int ie_sp_unpack_o(const void* xo, void* o_local, int64_t B, int64_t Sl, int32_t Hq, int32_t D, int32_t P,
                    void* stream);
 
-/* Backward (Sec. 3.1: the same two exchanges run in the backward pass).  Each is the inverse
+/* Backward (Sec. 3.2.2: the same two exchanges run in the backward pass).  Each is the inverse
  * permutation of a forward function, applied to the gradient that flows the other way:
  *   ie_sp_pack_do     inverts ie_sp_unpack_o :  xo[p][b][s][hl][:]  = dout_local[b][s][p*Hql + hl][:]
  *   ie_sp_unpack_do   inverts ie_sp_pack_o   :  dout[b][p*Sl + s][hl][:] = xo[p][b][s][hl][:]

@@ -6,7 +6,7 @@ imports nothing from the product package.
 
 Arrays are numpy float64, C-contiguous.  q, o, dout, dq: [B, S, Hq, D]; k, v, dk,
 dv: [B, S, Hkv, D]; lse: [B, Hq, S].  The arithmetic (exact softmax attention of the
-Transformer layer the paper runs per GPU over the full sequence, Sec. 2.1/2.2, and
+Transformer layer the paper runs per GPU over the full sequence, Sec. 2.1/2.4, and
 its analytic gradients) lives in the C file; this module only marshals arguments.
 """
 import ctypes

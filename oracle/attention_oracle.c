@@ -6,7 +6,7 @@
  * the product path may call it.
  *
  * What is computed (per batch b, query head h, kv head g = h / (Hq/Hkv)).
- * The method (Sec. 2.1 "Transformer Architecture", Sec. 2.2 "SP-2", Sec. 4.2
+ * The method (Sec. 2.1 "Transformer Architecture", Sec. 2.4 "SP-2", Sec. 4.2
  * "Computation Profiler": self-atten(b, S, H, D/s_sp) on one GPU) is the exact
  * multi-head softmax attention of the Transformer; the fused kernel the paper
  * names reaches exactly this result, so the oracle is the definition itself:

@@ -5,7 +5,7 @@ module), forward and backward.
 TEST INFRASTRUCTURE ONLY: imported by tests/ and by the cpu_baseline leg of bench.py.  Nothing on the
 product path may import it, and it imports nothing from the product package.
 
-A Linear module without bias (the models of Table 1 are LLaMA-style) with weight w [N, K] ("out, in") maps
+A Linear module without bias (the models of Table 2 are LLaMA-style) with weight w [N, K] ("out, in") maps
 x [M, K] (M = b * S/s_sp tokens) to
     y  = x w^T                 [M, N]
 and its backward pass, given dy [M, N], returns

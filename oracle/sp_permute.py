@@ -5,7 +5,7 @@ the product path may import it, and it imports nothing from the product package.
 
 With sequence parallelism of degree P every module but attention holds S/P tokens of all heads and
 attention holds all S tokens of heads/P heads; two all-to-alls per layer and direction change
-between the two (Sec. 2.2 "SP-2", Sec. 3.1 "Sequence Parallelism").  An all-to-all moves P equal
+between the two (Sec. 2.4 "SP-2", Sec. 3.2.2 "Sequence Parallelism").  An all-to-all moves P equal
 contiguous chunks, chunk p to and from peer p, so each exchange needs a permutation before it
 ("pack") and one after it ("unpack").  Each function below is that permutation written as numpy
 reshape / transpose / concatenate on arrays of 16-bit patterns (any dtype works; nothing is
@@ -47,7 +47,7 @@ def _concat_planes(q, k, v, lead):
 
 
 def pack_qkv(qkv_local, B, Sl, Hq, Hkv, D, P):
-    """xqkv[p][b][t][s][hl][:] = qkv_local[b][t][s][p*Hl_t + hl][:]  (Sec. 2.2 "SP-2")."""
+    """xqkv[p][b][t][s][hl][:] = qkv_local[b][t][s][p*Hl_t + hl][:]  (Sec. 2.4 "SP-2")."""
     out = []
     for plane, H in zip(_planes_of_qkv_local(qkv_local, B, Sl, Hq, Hkv, D), (Hq, Hkv, Hkv)):
         x = plane.reshape(B, Sl, P, H // P, D)          # head = p*Hl + hl

@@ -1,5 +1,5 @@
 """torch.autograd face of the kernels: `attention(q, k, v, ...)` runs ie_attn_fwd and, in backward, ie_attn_bwd
-on the saved o and log-sum-exp (the probabilities are recomputed, Sec. 3.1); `linear(x, w)` runs the three
+on the saved o and log-sum-exp (the probabilities are recomputed, Sec. 3.2); `linear(x, w)` runs the three
 products of a Linear module without bias (Sec. 4.2).  Only tensor bookkeeping happens here; there is no
 fallback path."""
 import torch
@@ -22,7 +22,7 @@ class _Attention(torch.autograd.Function):
 
     @staticmethod
     def backward(ctx, dout, _dlse):
-        if len(ctx.saved_tensors) == 3:   # activation recomputation: an additional forward pass (Sec. 2.1)
+        if len(ctx.saved_tensors) == 3:   # activation recomputation: an additional forward pass (Sec. 2.3)
             q, k, v = ctx.saved_tensors
             o, lse = binding.attn_fwd(q, k, v, ctx.scale, ctx.causal, ctx.cu_seqlens)
         else:
@@ -37,7 +37,7 @@ def attention(q, k, v, scale=None, causal=True, cu_seqlens=None, return_lse=Fals
     in q, k and v.  `cu_seqlens` (int32, on the GPU) packs several documents into one sequence (B = 1).
     `workspace`: a uint8 GPU tensor for the backward pass, typically one binding.alloc_bwd_workspace(q, k,
     fast=True) shared by all layers, which selects the backward path that stores dS; by default a small one
-    is allocated per call.  `recompute`: activation recomputation for this module (Sec. 2.1) — o and the log-sum-exp
+    is allocated per call.  `recompute`: activation recomputation for this module (Sec. 2.3) — o and the log-sum-exp
     are not kept for the backward pass, which runs the forward kernel once more instead (bit-identical values)."""
     if scale is None:
         scale = q.shape[-1] ** -0.5

@@ -8,8 +8,6 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libie_attn.so")
-PEAK_PROBE = os.path.join(HERE, "mfma_peak_probe")   # standalone executable: sustained MFMA rate of the device
-ISSUE_PROBE = os.path.join(HERE, "issue_cost_probe")  # standalone executable: what fits in an MFMA's shadow
 SOURCES = ["ie_attn_api.hip", "attn_fwd.hip", "attn_fwd_wide.hip", "attn_bwd.hip", "sp_permute.hip", "linear_gemm.hip"]
 # -fno-honor-nans: the kernels never produce NaN from finite inputs (masked scores are -inf and only ever
 # meet finite references), and without it every max is preceded by a canonicalising self-max.
@@ -85,14 +83,6 @@ def build(verbose=False, extra=()):
     missing = [l.split()[-1] for l in r.stdout.splitlines() if "_ZN2ie" in l]
     if missing:
         raise RuntimeError("libie_attn.so has undefined symbols of its own namespace: " + ", ".join(missing))
-    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-o", PEAK_PROBE, os.path.join(CSRC, "mfma_peak_probe.hip")],
-                       capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("mfma_peak_probe failed to build:\n" + r.stderr)
-    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                        "-o", ISSUE_PROBE, os.path.join(CSRC, "issue_cost_probe.hip")], capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("issue_cost_probe failed to build:\n" + r.stderr)
     return LIB
 
 

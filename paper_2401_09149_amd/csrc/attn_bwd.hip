@@ -1,6 +1,6 @@
 // Backward kernels.  The probabilities are recomputed from the saved log-sum-exp (the
-// fused kernel's selective recomputation, Sec. 3.1), and the five products of the
-// backward pass (Sec. 4.3: backward is the compute-heavier direction) are split over two
+// fused kernel's selective recomputation, Sec. 3.2), and the five products of the
+// backward pass (the appendix "Implementation Detail: Selective Overlap": backward is the compute-heavier direction) are split over two
 // kernels so that each output has exactly one owner and nothing is accumulated through
 // memory:
 //   attn_bwd_delta : delta_i = <dO_i, O_i>                              (HBM-bound)
@@ -667,10 +667,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     }
   };
 
-#ifdef IE_EXP_TIMING
-  uint64_t t_fast = 0, t_gen = 0, t_sync = 0, n_fast = 0;
-  const uint64_t t_begin = __builtin_readcyclecounter();
-#endif
   // One step = one query tile of one query head.  `slot` (compile-time) is the stage that holds it.
   int hq_idx = 0, tile_idx = 0;  // the step being computed
   auto step_fn = [&](const int st, auto slot_c) __attribute__((always_inline)) {
@@ -684,9 +680,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     // Mask when a key of this wave can exceed a row of the tile (causal) or rows run past the document.
     const bool need_mask = (p.causal && wv * 32 + 31 > i0) || (i0 + BQ > nq);
     const bool fast = D == 128 && !need_mask;
-#ifdef IE_EXP_TIMING
-    const uint64_t tt0 = __builtin_readcyclecounter();
-#endif
     if (fast && next_full) {
       fast_tile(sp[slot], next, std::true_type{});
     } else {
@@ -694,19 +687,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
       if (fast) fast_tile(sp[slot], next, std::false_type{});
       else generic_tile(sp[slot], i0);
     }
-#ifdef IE_EXP_TIMING
-    const uint64_t tt1 = __builtin_readcyclecounter();
-    if (fast) { t_fast += tt1 - tt0; n_fast += 1; } else { t_gen += tt1 - tt0; }
-#endif
     // The next tile's copies have landed; vector memory operations complete in issue order, and after a
     // hand-sequenced tile that copied piece by piece the six youngest are the dS stores of its last three
     // 32-row blocks, which nothing in this kernel waits for.
     if (STORE_DS && fast && next_full) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
     else async_wait_all();
     __syncthreads();
-#ifdef IE_EXP_TIMING
-    t_sync += __builtin_readcyclecounter() - tt1;
-#endif
     if (STORE_DS) {
       if (next_tile == 0) { ds_first += ds_head; ds_step = ds_first; }
       else ds_step += ds_matrix_bytes(p.S / BQ, it0 + tile_idx, p.causal != 0);
@@ -718,9 +704,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   agpr_loads_wait();  // K/V fragments (and the first stage's copies) have arrived
   async_wait_all();
   __syncthreads();
-#ifdef IE_EXP_TIMING
-  const uint64_t t_ready = __builtin_readcyclecounter();
-#endif
   int st = 0;
   for (; st + 1 < total; st += 2) {
     step_fn(st, std::integral_constant<int, 0>{});
@@ -729,14 +712,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   if (st < total) step_fn(st, std::integral_constant<int, 0>{});
   if (pending) flush_pending();
   mfma_result_fence();  // the last assembly MFMAs have retired before the accumulators are read
-#ifdef IE_EXP_TIMING
-  if (tid == 0) {
-    uint64_t* dbg = reinterpret_cast<uint64_t*>(p.dq) + (size_t)item * 8;
-    dbg[0] = __builtin_readcyclecounter() - t_begin; dbg[1] = t_fast; dbg[2] = n_fast; dbg[3] = t_gen; dbg[4] = t_sync; dbg[5] = total;
-    dbg[6] = t_ready - t_begin;   // waiting for K/V fragments and the first stage
-    dbg[7] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));  // HW_ID
-  }
-#endif
 
   const int64_t key_st = key_ok ? key : tc.doc_end - 1;  // (address only formed for rows that exist)
   __bf16* dkrow = p.dk + kvhead + key_st * kv_stride;

@@ -211,9 +211,7 @@ static int launch_fwd_d(AttnParams p, hipStream_t st) {
 }
 
 int launch_fwd(AttnParams p, int D, hipStream_t st) {
-#ifndef IE_EXP_FWD_NARROW
   if (D == 128) return launch_fwd_wide(p, st);
-#endif
   return D == 64 ? launch_fwd_d<64>(p, st) : launch_fwd_d<128>(p, st);
 }
 

@@ -245,17 +245,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
                    auto kload_c, auto vload_c, const bool copying, const CopySrc& cs, auto slot_c)
       __attribute__((always_inline)) {
     constexpr bool HAS_S = decltype(has_s)::value, HAS_PV = decltype(has_pv)::value;
-#ifdef IE_EXP_W_NOSM
-    constexpr bool HAS_SM = false;
-#else
     constexpr bool HAS_SM = decltype(has_sm)::value;
-#endif
-#ifdef IE_EXP_W_NOLDS
-    constexpr int vpar = decltype(vpar_c)::value, kload_off = -1, vload_off = -1;
-#else
     constexpr int vpar = decltype(vpar_c)::value, kload_off = decltype(kload_c)::value;
     constexpr int vload_off = decltype(vload_c)::value;
-#endif
     constexpr int copy_slot = decltype(slot_c)::value;
     bf16x8 pf0, pf1;
 #pragma unroll
@@ -316,11 +308,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   // One round: the eight phases that read tile T (stage STG).  `copy_tile` is T + 1 when that
   // tile is complete and is to be copied piece by piece during the round, else -1.
   auto round = [&](auto stg_c, auto first_c, const int copy_tile) __attribute__((always_inline)) {
-#ifdef IE_EXP_W_NOCOPY
-    copying = false;
-#else
     copying = copy_tile >= 0;
-#endif
     if (copying) cs = copy_src(copy_tile);
     constexpr int STG = decltype(stg_c)::value;
     constexpr bool FIRST = decltype(first_c)::value;
@@ -467,20 +455,10 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   __syncthreads();
   stagger();
 
-#ifdef IE_EXP_TIMING
-  const unsigned long long t_begin = __builtin_readcyclecounter(), w_begin = wall_clock64();
-  unsigned long long t_sync = 0, t_fast = 0;
-#endif
   auto end_of_tile = [&]() __attribute__((always_inline)) {
-#ifdef IE_EXP_TIMING
-    const unsigned long long ts0 = __builtin_readcyclecounter();
-#endif
     async_wait_all();  // this wave's copies of the next tile have landed ...
     __syncthreads();   // ... everyone's have, and everyone is done reading this stage
     stagger();
-#ifdef IE_EXP_TIMING
-    t_sync += __builtin_readcyclecounter() - ts0;
-#endif
   };
   // Starts the copy of tile T + 1 unless it is left to the round (a complete tile, piece by
   // piece); returns the tile the round has to copy, or -1.
@@ -509,9 +487,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
     }
     drain();
   }
-#ifdef IE_EXP_TIMING
-  t_fast = __builtin_readcyclecounter() - t_begin;
-#endif
   for (; T < nkt; ++T) {
     if (T + 1 < nkt) copy_all(T + 1);
     generic_tile(T);
@@ -526,27 +501,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
     __bf16* orow = p.o_out + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D + row * q_stride;
 #pragma unroll
     for (int db = 0; db < NDB; ++db) store_block32_bf16(orow + 32 * db, o[db], inv_l, h, ok);
-#ifndef IE_EXP_TIMING
     if (ok && h == 0) p.lse_out[((int64_t)tc.b * p.Hq + tc.h) * p.S + row] = (st.m * c + __builtin_amdgcn_logf(l_full)) * kLn2;
-#endif
   };
   // (the rows are formed again from their 32-bit positions: two 64-bit row indices kept alive
   // through the whole kernel are four registers this kernel does not have)
   store(oa, sa, k_begin + rel_a, ok_a);
   store(ob, sb, k_begin + rel_b, ok_b);
-#ifdef IE_EXP_TIMING
-  if (lane == 0) {  // timing build: the lse buffer carries per-wave counters instead
-    unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.lse_out) + ((size_t)item * 4 + wv) * 8;
-    dbg[0] = __builtin_readcyclecounter() - t_begin;
-    dbg[1] = wall_clock64() - w_begin;
-    dbg[2] = nkt; dbg[4] = t_sync; dbg[5] = t_fast;
-    uint32_t xcc_raw, hw;   // where the wave ran: XCD number, and the hardware id (CU, shader array, shader engine)
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)\n\ts_getreg_b32 %1, hwreg(HW_REG_HW_ID)" : "=s"(xcc_raw), "=s"(hw));
-    dbg[7] = ((unsigned long long)xcc_raw << 32) | hw;
-    dbg[3] = n_fast;
-    dbg[6] = w_begin;   // 100 MHz counter after the prologue; + dbg[1] = at exit
-  }
-#endif
   }  // next item
 }
 

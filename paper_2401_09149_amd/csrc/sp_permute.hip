@@ -1,5 +1,5 @@
 // The eight local re-layouts either side of the sequence-parallel all-to-alls (include/ie_sp.h;
-// Sec. 2.2 "SP-2", Sec. 3.1 "Sequence Parallelism").  Every one of them moves contiguous runs of
+// Sec. 2.4 "SP-2", Sec. 3.2.2 "Sequence Parallelism").  Every one of them moves contiguous runs of
 // Hl*D bf16 values (one token's heads of one head group) between two 4-level strided layouts
 // indexed by (peer p, batch b, token s of the slice, position in the run), so one kernel serves
 // all: a "plane" descriptor gives the strides of both sides, and the q, k and v planes of the

@@ -15,7 +15,7 @@ and the sharding factors of parameters, gradients and optimizer states.  This mo
 
 Readings where the paper is at odds with itself (each is pinned by a test):
   * The summary equation for M_tf divides G and OS by s_gs and s_oss only and weighs P, G and OS alike;
-    the text of Sec. 3.2.3 divides G by s_ps * s_gs and OS by s_ps * s_oss, and Table 3 gives OS three times
+    the text of Sec. 3.2.3 divides G by s_ps * s_gs and OS by s_ps * s_oss, and Table 2 gives OS three times
     the bytes of P.  The text and the table are followed (with the summary equation the paper's own plan for
     65B at 256K would need 130 GB of an 80 GB GPU).
   * "When a = 1 ... 2bSH ... Conversely, if a = 1 ... 34bSH": the second is a = 0, as in the equation
@@ -33,7 +33,7 @@ from dataclasses import dataclass
 
 @dataclass(frozen=True)
 class Model:
-    """Table 3: hidden size, layers, attention heads, vocabulary."""
+    """Table 2: hidden size, layers, attention heads, vocabulary."""
     name: str
     H: int
     L: int
@@ -42,7 +42,7 @@ class Model:
 
     @property
     def psi(self):
-        """Parameters of one Transformer layer (Table 3)."""
+        """Parameters of one Transformer layer (Table 2)."""
         return 12 * self.H * self.H + 2 * self.H
 
 
@@ -66,7 +66,7 @@ class Plan:
 
 def violated_constraints(plan, model, N, B_tokens, S):
     """Names of the constraints `plan` breaks (empty list: feasible apart from memory).  Sec. 4.5, Eq. (3)-(8);
-    Sec. 3.2.3 (ranges of the sharding factors, Config-1/2); Sec. 5.3 (heads divisible by s_sp)."""
+    Sec. 3.2.3 (ranges of the sharding factors, Config-1/2); Sec. 5.4 (heads divisible by s_sp)."""
     p, bad = plan, []
     if min(p.b, p.n, p.s_pp, p.s_dp, p.s_tp, p.s_sp, p.s_ps, p.s_gs, p.s_oss) < 1 or p.a not in (0, 1):
         return ["positive"]

@@ -3,7 +3,7 @@
 The paper's computation profiler measures `self-atten(b, S, H, D/s_sp)` on a single GPU for the
 shapes its planner considers (Sec. 4.2 "Computation Profiler"); this is that sweep for the plans
 the paper lists as its own choice ("Our Work" rows of Appendix Tables 4-7): micro-batch b, all S
-tokens, heads/s_sp heads of dimension 128 (Table 1: 32, 40, 48 and 64 heads).  Inputs are N(0,1)
+tokens, heads/s_sp heads of dimension 128 (Table 2: 32, 40, 48 and 64 heads).  Inputs are N(0,1)
 rounded to bf16, drawn on the device (timing only; parity is the tests' business).  The backward pass is
 timed twice: with the small workspace (dQ recomputes S, P, dP) and, where B*Hq*S*(S+128) bytes more fit the
 limit given by --ds-limit-gb, with the workspace that lets the dK/dV kernel store dS.

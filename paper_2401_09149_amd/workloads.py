@@ -2,7 +2,7 @@
 
 Holds no attention arithmetic: only shapes, seeds and random draws, so that the CPU
 oracle (tests) and the HIP path consume the same bytes.  The five configurations are
-the per-GPU shapes that hybrid sequence parallelism (Sec. 2.2 "SP-2", Sec. 3.1
+the per-GPU shapes that hybrid sequence parallelism (Sec. 2.4 "SP-2", Sec. 3.2.2
 "Sequence Parallelism") gives one GPU: all S tokens of heads/s_sp heads, head
 dimension 128 as in every model of Table 2.  The paper evaluates throughput only and
 names no dataset, so N(0,1) activations stand in for real ones.
@@ -106,7 +106,7 @@ def bwd_flops(cfg, cu_seqlens=None):
 
 @dataclass(frozen=True)
 class SpConfig:
-    """One GPU's buffers around the two all-to-alls of a layer (Sec. 2.2 "SP-2", Sec. 3.1): micro-batch B,
+    """One GPU's buffers around the two all-to-alls of a layer (Sec. 2.4 "SP-2", Sec. 3.2.2): micro-batch B,
     Sl = S/P tokens per sequence slice, Hq / Hkv heads of the whole layer, P = s_sp peers."""
     name: str
     index: int

@@ -79,7 +79,7 @@ def test_output_columns_that_are_multiples_of_8_only():
 @pytest.mark.parametrize("M,N,K", [(8192, 12288, 4096), (16384, 22016, 8192)])
 def test_paper_shapes_sampled(M, N, K):
     """7B QKV projection at one GPU's 8192 tokens (hidden 4096), and the 65B gate/up projection whose output is the
-    (16384, 22016) activation of the appendix on memory fragmentation (hidden 8192; Table 1): whole outputs against
+    (16384, 22016) activation of the appendix on memory fragmentation (hidden 8192; Table 2): whole outputs against
     the oracle would take minutes of float64 matmul, so 64 sampled rows of each output are compared."""
     x, w, dy = randn_bf16((M, K), 21), randn_bf16((N, K), 22), randn_bf16((M, N), 23)
     xd, wd, dyd = x.to(DEV), w.to(DEV), dy.to(DEV)

@@ -1,5 +1,5 @@
 """Pins of the permute oracle (oracle/sp_permute.py) to what the paper fixes about the two
-sequence-parallel all-to-alls (Sec. 2.2 "SP-2", Sec. 3.1 "Sequence Parallelism"):
+sequence-parallel all-to-alls (Sec. 2.4 "SP-2", Sec. 3.2.2 "Sequence Parallelism"):
 
   - after pack -> all-to-all -> unpack every GPU holds the COMPLETE sequence of Q, K and V for its
     subset of the heads, and after attention the second exchange re-partitions the result along
@@ -149,7 +149,7 @@ def test_index_formulas_by_brute_force():
 
 def test_exchange_volumes_match_the_paper():
     """Per layer and direction the first exchange moves 6bSH bytes over the group and the second 2bSH
-    (Sec. 3.1, with H the hidden size and 2-byte elements): per GPU that is 1/P of it."""
+    (Sec. 3.2.2, with H the hidden size and 2-byte elements): per GPU that is 1/P of it."""
     B, Sl, Hq, D, P = 2, 8, 4, 8, 2
     S, hidden = P * Sl, Hq * D
     x = sp.pack_qkv(np.zeros(B * Sl * 3 * Hq * D, np.uint16), B, Sl, Hq, Hq, D, P)

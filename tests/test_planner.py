@@ -1,4 +1,4 @@
-"""Pins of the planner slice (paper_2401_09149_amd/planner.py) to what the paper prints: Table 3 (model sizes),
+"""Pins of the planner slice (paper_2401_09149_amd/planner.py) to what the paper prints: Table 2 (model sizes),
 the memory and communication equations of Sec. 3.2, the constraints of Sec. 4.5, and the paper's own plans
 (Appendix Tables 4-7, tests/golden/paper_plans.csv): each of them must satisfy every constraint and fit the
 80 GB GPUs it was run on.  The search is checked against an independent brute-force enumeration."""
@@ -10,7 +10,7 @@ import pytest
 from paper_2401_09149_amd import planner as pl
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-N, B_TOKENS, CAP = 128, 2 ** 22, 80e9     # Sec. 5.1: 128 GPUs of 80 GB; the plans' b * S * n * s_dp is 4Mi tokens
+N, B_TOKENS, CAP = 128, 2 ** 22, 80e9     # Sec. 5.1: 128 GPUs of 80 GB; Sec. 5.2: global batch of 4M tokens = the plans' b * S * n * s_dp
 
 
 def paper_plans():
@@ -48,7 +48,7 @@ def test_memory_equations():
     base = pl.Plan(b=1, n=4, a=0, s_pp=1, s_dp=128, s_tp=1, s_sp=1, s_ps=1, s_gs=1, s_oss=1)
     S = 32768
     mem = pl.memory_bytes(base, m, S)
-    # Table 3: P and G take 2 bytes per parameter, OS 6; activations 34 b S H per layer without recomputation
+    # Table 2: P and G take 2 bytes per parameter, OS 6; activations 34 b S H per layer without recomputation
     assert mem["P"] == 2 * m.L * m.psi and mem["G"] == mem["P"] and mem["OS"] == 3 * mem["P"]
     assert mem["ACT"] == 34 * S * m.H * m.L
     rec = pl.memory_bytes(pl.Plan(1, 4, 1, 1, 128, 1, 1, 1, 1, 1), m, S)
