@@ -3,8 +3,8 @@
 
 A step is one pass of the whole path (forward, then backward: delta, dK/dV, dQ) over one
 batch of seeded synthetic input that is already resident in HBM.  The backward pass gets the
-workspace of ie_attn_bwd_fast_workspace_bytes (room for dS, B*Hq*S*(S+128) bytes more) unless
---recompute-ds is given: with it the dK/dV kernel stores dS and dQ is one product instead of three.  The workload is the
+O(S) workspace of ie_attn_bwd_workspace_bytes; the optional path that keeps dS in B*Hq*S*(S+128) bytes more
+is timed beside it and reported under bwd.other_path (--stored-ds swaps the two).  The workload is the
 7B-class layer with all heads on one GPU: B=1, S=32768, Hq=Hkv=32, D=128, causal, bf16.
 FLOP convention: forward = 4*S^2*D*Hq / 2 (causal halving), backward = 2.5x forward.
 
@@ -234,8 +234,9 @@ def main():
     ap.add_argument("--cpu-heads", type=int, default=1)
     ap.add_argument("--sp-config", type=int, default=1, help="index into the re-layout workload table; -1 skips that part")
     ap.add_argument("--no-linear", action="store_true", help="skip the linear-module part")
-    ap.add_argument("--recompute-ds", action="store_true",
-                    help="give the backward pass the small workspace only: dQ recomputes S, P and dP instead of reading a stored dS")
+    ap.add_argument("--stored-ds", action="store_true",
+                    help="time the optional backward path that keeps dS in a B*Hq*S*(S+128)-byte workspace as the step's backward "
+                         "(default: the O(S)-workspace path; the other one is reported under bwd.other_path)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -259,14 +260,18 @@ def main():
     o = torch.empty_like(q)
     lse = torch.empty((cfg.B, cfg.Hq, cfg.S), dtype=torch.float32, device=dev)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    ws = binding.alloc_bwd_workspace(q, k, cu, fast=not args.recompute_ds, causal=cfg.causal)
-    stored_ds = ws.numel() > binding.ie_attn_bwd_workspace_bytes(cfg.B, cfg.S, cfg.Hq, cfg.Hkv, cfg.D, 0 if cu is None else cu.numel() - 1)
+    nd = 0 if cu is None else cu.numel() - 1
+    small_bytes = binding.ie_attn_bwd_workspace_bytes(cfg.B, cfg.S, cfg.Hq, cfg.Hkv, cfg.D, nd)
+    ds_bytes = binding.ie_attn_bwd_fast_workspace_bytes(cfg.B, cfg.S, cfg.Hq, cfg.Hkv, cfg.D, nd, cfg.causal)
+    has_ds_path = ds_bytes > small_bytes
+    stored_ds = args.stored_ds and has_ds_path
+    ws = binding.alloc_bwd_workspace(q, k, cu, fast=stored_ds, causal=cfg.causal)
 
     def fwd():
         binding.ie_attn_fwd(q, k, v, o, lse, cu, cfg.scale, cfg.causal)
 
     def bwd(phases=binding.BWD_ALL):
-        binding.ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu, cfg.scale, cfg.causal, ws, phases)
+        binding.ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu, cfg.scale, cfg.causal, ws, phases, stored_ds=stored_ds)
 
     def step():
         fwd()
@@ -297,18 +302,19 @@ def main():
     dkdv_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DKDV), it)
     dq_ms, _, _ = event_ms(lambda: bwd(binding.BWD_DQ), it)   # (with a stored dS: reads what the dK/dV phase just left)
 
-    # the other backward path (small workspace: dQ recomputes S, P, dP), for comparison; not part of `value`
+    # the other backward path, for comparison; not part of `value`
     other = None
-    if stored_ds:
-        ws_small = binding.alloc_bwd_workspace(q, k, cu)
-        bwd_small = lambda ph=binding.BWD_ALL: binding.ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu, cfg.scale,
-                                                                          cfg.causal, ws_small, ph)
-        bwd_small()
-        o_ms, _, _ = event_ms(bwd_small, it)
-        o_dq, _, _ = event_ms(lambda: bwd_small(binding.BWD_DQ), it)
-        o_dkdv, _, _ = event_ms(lambda: bwd_small(binding.BWD_DKDV), it)
-        other = {"path": "recompute", "ms": o_ms, "dq_ms": o_dq, "dkdv_ms": o_dkdv, "workspace_bytes": ws_small.numel()}
-        del ws_small
+    if has_ds_path and (stored_ds or ds_bytes <= 64e9):
+        ws_o = binding.alloc_bwd_workspace(q, k, cu, fast=not stored_ds, causal=cfg.causal)
+        bwd_o = lambda ph=binding.BWD_ALL: binding.ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu, cfg.scale,
+                                                                      cfg.causal, ws_o, ph, stored_ds=not stored_ds)
+        bwd_o()
+        o_ms, _, _ = event_ms(bwd_o, it)
+        o_dkdv, _, _ = event_ms(lambda: bwd_o(binding.BWD_DKDV), it)
+        o_dq, _, _ = event_ms(lambda: bwd_o(binding.BWD_DQ), it)
+        other = {"path": "recompute" if stored_ds else "stored_ds", "ms": o_ms, "dq_ms": o_dq, "dkdv_ms": o_dkdv,
+                 "tflops": W.bwd_flops(cfg, cu_np) / (o_ms * 1e-3) / 1e12, "workspace_bytes": ws_o.numel()}
+        del ws_o
 
     f_fwd = W.fwd_flops(cfg, cu_np)
     f_bwd = W.bwd_flops(cfg, cu_np)

@@ -64,7 +64,8 @@ typedef enum ie_attn_status {
   IE_ERR_UNSUPPORTED = -3, /* D not in {64,128}; scale not finite or <= 0; causal not 0/1 */
   IE_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned (256 B) or smaller than ie_attn_bwd_workspace_bytes */
   IE_ERR_HIP = -5,         /* a HIP call failed; ie_attn_last_hip_error() has the runtime's text */
-  IE_ERR_ALIGN = -6        /* a pointer is not 16-byte aligned (ie_sp.h) */
+  IE_ERR_ALIGN = -6,       /* a pointer is not 16-byte aligned (ie_sp.h) */
+  IE_ERR_BUSY = -7         /* ie_attn_fwd: all work-queue slots are in flight or held by captured graphs (see above) */
 } ie_attn_status;
 
 /*
@@ -122,7 +123,7 @@ int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
  * and IE_BWD_DQ needs it: run IE_BWD_DKDV before IE_BWD_DQ there.  ie_attn_bwd(...) is ie_attn_bwd_phases(..., IE_BWD_ALL).  A mask of 0 or with
  * other bits set is IE_ERR_UNSUPPORTED.
  */
-enum { IE_BWD_DELTA = 1, IE_BWD_DQ = 2, IE_BWD_DKDV = 4, IE_BWD_ALL = 7 };
+enum { IE_BWD_DELTA = 1, IE_BWD_DQ = 2, IE_BWD_DKDV = 4, IE_BWD_ALL = 7, IE_BWD_STORED_DS = 16 };
 int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* dout,
                        const float* lse, void* dq, void* dk, void* dv,
                        const int32_t* cu_seqlens, int32_t num_docs,

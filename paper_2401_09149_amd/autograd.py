@@ -9,14 +9,14 @@ from . import binding
 
 class _Attention(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, q, k, v, scale, causal, cu_seqlens, workspace, recompute):
+    def forward(ctx, q, k, v, scale, causal, cu_seqlens, workspace, recompute, stored_ds):
         q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
         o, lse = binding.attn_fwd(q, k, v, scale, causal, cu_seqlens)
         if recompute:   # keep the inputs only; the outputs handed to the caller are not referenced from here
             ctx.save_for_backward(q, k, v)
         else:
             ctx.save_for_backward(q, k, v, o, lse)
-        ctx.cu_seqlens, ctx.scale, ctx.causal, ctx.workspace = cu_seqlens, scale, causal, workspace
+        ctx.cu_seqlens, ctx.scale, ctx.causal, ctx.workspace, ctx.stored_ds = cu_seqlens, scale, causal, workspace, stored_ds
         ctx.mark_non_differentiable(lse)
         return o, lse
 
@@ -28,20 +28,21 @@ class _Attention(torch.autograd.Function):
         else:
             q, k, v, o, lse = ctx.saved_tensors
         dq, dk, dv = binding.attn_bwd(q, k, v, o, dout.contiguous(), lse, ctx.scale, ctx.causal, ctx.cu_seqlens,
-                                      workspace=ctx.workspace)
-        return dq, dk, dv, None, None, None, None, None
+                                      workspace=ctx.workspace, stored_ds=ctx.stored_ds)
+        return dq, dk, dv, None, None, None, None, None, None
 
 
-def attention(q, k, v, scale=None, causal=True, cu_seqlens=None, return_lse=False, workspace=None, recompute=False):
+def attention(q, k, v, scale=None, causal=True, cu_seqlens=None, return_lse=False, workspace=None, recompute=False,
+              stored_ds=False):
     """Exact softmax attention of q [B,S,Hq,D] against k, v [B,S,Hkv,D] (bf16, on the GPU), differentiable
     in q, k and v.  `cu_seqlens` (int32, on the GPU) packs several documents into one sequence (B = 1).
-    `workspace`: a uint8 GPU tensor for the backward pass, typically one binding.alloc_bwd_workspace(q, k,
-    fast=True) shared by all layers, which selects the backward path that stores dS; by default a small one
-    is allocated per call.  `recompute`: activation recomputation for this module (Sec. 2.3) — o and the log-sum-exp
+    `workspace`: a uint8 GPU tensor for the backward pass, typically one binding.alloc_bwd_workspace(q, k)
+    shared by all layers; by default one is allocated per call.  `stored_ds`: take the backward path that keeps dS
+    in the workspace (binding.alloc_bwd_workspace(q, k, fast=True): B*Hq*S*(S+128) bytes more).  `recompute`: activation recomputation for this module (Sec. 2.3) — o and the log-sum-exp
     are not kept for the backward pass, which runs the forward kernel once more instead (bit-identical values)."""
     if scale is None:
         scale = q.shape[-1] ** -0.5
-    o, lse = _Attention.apply(q, k, v, float(scale), bool(causal), cu_seqlens, workspace, bool(recompute))
+    o, lse = _Attention.apply(q, k, v, float(scale), bool(causal), cu_seqlens, workspace, bool(recompute), bool(stored_ds))
     return (o, lse) if return_lse else o
 
 

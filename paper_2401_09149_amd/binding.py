@@ -12,7 +12,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("IE_ATTN_LIB") or os.path.join(_HERE, "libie_attn.so")  # override: for trying out a build
 
-EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd_fast_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases", "ie_attn_strerror",
+EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd_fast_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases",
+           "ie_attn_strerror",
            "ie_attn_last_hip_error",
            "ie_sp_pack_qkv", "ie_sp_unpack_qkv", "ie_sp_pack_o", "ie_sp_unpack_o",
            "ie_sp_pack_do", "ie_sp_unpack_do", "ie_sp_pack_dqkv", "ie_sp_unpack_dqkv",
@@ -92,10 +93,21 @@ def _stream(stream):
     return (stream if stream is not None else torch.cuda.current_stream()).cuda_stream
 
 
-def _shape(q, k):
+def _shape(q, k, **others):
+    """B, S, Hq, Hkv, D of the call; `others`: further tensors by role (v, o, dout, dq like q; dk, dv like k; lse).
+    The C ABI sees pointers only, so every shape is checked here: a kernel handed a smaller buffer would read or
+    write past its end."""
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("q and k must be [B, S, heads, D]")
     B, S, Hq, D = q.shape
     if k.shape[0] != B or k.shape[1] != S or k.shape[3] != D:
         raise ValueError("q and k disagree on B, S or D")
+    for name, t in others.items():
+        if t is None:
+            continue
+        want = (B, Hq, S) if name == "lse" else tuple(k.shape) if name in ("v", "dk", "dv") else tuple(q.shape)
+        if tuple(t.shape) != want:
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {want}")
     return B, S, Hq, k.shape[2], D
 
 
@@ -115,7 +127,7 @@ def ie_attn_bwd_fast_workspace_bytes(B, S, Hq, Hkv, D, num_docs=0, causal=True):
 
 def ie_attn_fwd(q, k, v, o, lse, cu_seqlens, scale, causal, stream=None):
     """o[B,S,Hq,D] bf16 and lse[B,Hq,S] fp32 are overwritten; all tensors live on the GPU."""
-    B, S, Hq, Hkv, D = _shape(q, k)
+    B, S, Hq, Hkv, D = _shape(q, k, v=v, o=o, lse=lse)
     cu, nd = _docs(cu_seqlens)
     bf = torch.bfloat16
     rc = load().ie_attn_fwd(_ptr(q, bf, "q"), _ptr(k, bf, "k"), _ptr(v, bf, "v"), _ptr(o, bf, "o"),
@@ -126,16 +138,20 @@ def ie_attn_fwd(q, k, v, o, lse, cu_seqlens, scale, causal, stream=None):
 
 
 BWD_DELTA, BWD_DQ, BWD_DKDV, BWD_ALL = 1, 2, 4, 7
+BWD_STORED_DS = 16
 
 
-def ie_attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, stream=None):
-    """dq, dk, dv are overwritten; `workspace` is a uint8 GPU tensor of ie_attn_bwd_workspace_bytes(...)."""
-    ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, BWD_ALL, stream)
+def ie_attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, stream=None, stored_ds=False):
+    """dq, dk, dv are overwritten; `workspace` is a uint8 GPU tensor of ie_attn_bwd_workspace_bytes(...), or of
+    ie_attn_bwd_fast_workspace_bytes(...) with `stored_ds`."""
+    ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, BWD_ALL, stream, stored_ds)
 
 
-def ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, phases, stream=None):
-    """Selected kernels of the backward pass (bit mask of BWD_DELTA, BWD_DQ, BWD_DKDV)."""
-    B, S, Hq, Hkv, D = _shape(q, k)
+def ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, phases, stream=None,
+                       stored_ds=False):
+    """Selected kernels of the backward pass (bit mask of BWD_DELTA, BWD_DQ, BWD_DKDV); `stored_ds` adds the flag
+    that selects the path which keeps dS in the workspace."""
+    B, S, Hq, Hkv, D = _shape(q, k, v=v, o=o, dout=dout, lse=lse, dq=dq, dk=dk, dv=dv)
     cu, nd = _docs(cu_seqlens)
     bf = torch.bfloat16
     ws = _ptr(workspace, torch.uint8, "workspace")
@@ -143,7 +159,7 @@ def ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, cau
                             _ptr(dout, bf, "dout"), _ptr(lse, torch.float32, "lse"), _ptr(dq, bf, "dq"),
                             _ptr(dk, bf, "dk"), _ptr(dv, bf, "dv"), cu, nd, B, S, Hq, Hkv, D, float(scale),
                             int(bool(causal)), ws, workspace.numel() if workspace is not None else 0,
-                            int(phases), _stream(stream))
+                            int(phases) | (BWD_STORED_DS if stored_ds else 0), _stream(stream))
     if rc != 0:
         _raise(rc)
 
@@ -167,11 +183,11 @@ def alloc_bwd_workspace(q, k, cu_seqlens=None, fast=False, causal=True):
     return torch.empty(size, dtype=torch.uint8, device=q.device)
 
 
-def attn_bwd(q, k, v, o, dout, lse, scale, causal=True, cu_seqlens=None, workspace=None):
+def attn_bwd(q, k, v, o, dout, lse, scale, causal=True, cu_seqlens=None, workspace=None, stored_ds=False):
     if workspace is None:
-        workspace = alloc_bwd_workspace(q, k, cu_seqlens)
+        workspace = alloc_bwd_workspace(q, k, cu_seqlens, fast=stored_ds, causal=causal)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    ie_attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace)
+    ie_attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, workspace, stored_ds=stored_ds)
     return dq, dk, dv
 
 

@@ -75,7 +75,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
-  __shared__ int s_work;
+  __shared__ QueueState s_work;
+  queue_init(p, &s_work);
   const uint32_t xcc = xcc_id();
   int skip = 0;
   for (;;) {   // persistent: one item (batch, head, query tile) per iteration (tile_queue.hpp)
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   const int lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
 
-  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item);
+  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item, tid);
   if (!tc.valid) continue;
   const int g = tc.h / (p.Hq / p.Hkv);
   const int64_t q0 = tc.t0;
@@ -262,7 +263,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
-  __shared__ int s_work;
+  __shared__ QueueState s_work;
+  queue_init(p, &s_work);
   const uint32_t xcc = xcc_id();
   int skip = 0;
   for (;;) {   // persistent: one item (batch, kv head, key block) per iteration (tile_queue.hpp)
@@ -275,7 +277,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   const int lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
 
-  TileCoord tc = decode_tile<BK>(p, p.Hkv, false, scratch, item);
+  TileCoord tc = decode_tile<BK>(p, p.Hkv, false, scratch, item, tid);
   if (!tc.valid) continue;
   const int g = tc.h;
   const int group = p.Hq / p.Hkv;
@@ -746,7 +748,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
-  __shared__ int s_work;
+  __shared__ QueueState s_work;
+  queue_init(p, &s_work);
   const uint32_t xcc = xcc_id();
   int skip = 0;
   for (;;) {   // persistent: one item (batch, head, pair of query tiles) per iteration (tile_queue.hpp)
@@ -757,7 +760,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
   const int lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
 
-  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item);
+  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item, tid);
   if (!tc.valid) continue;
   const int g = tc.h / (p.Hq / p.Hkv);
   const int64_t q0 = tc.t0;
@@ -869,6 +872,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
   }  // next item
 }
 
+// Work-queue counters of the two main kernels inside the workspace's counter area (in 4-byte units).
+constexpr int kCountersDq = 0, kCountersDkdv = kQueueBytes / 4;
+
 template <int D>
 static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
   hipError_t e;
@@ -890,10 +896,11 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     if constexpr (D == 128) {
       if (from_ds) {
         constexpr int smem = 3 * 3 * 32 * D * 2;
-        int rc = set_smem(attn_bwd_dq_from_ds_kernel<D>, smem);
+        static KernelSetup setup;
+        int per_cu = 1;
+        int rc = kernel_setup(setup, attn_bwd_dq_from_ds_kernel<D>, smem, &per_cu);
         if (rc) return rc;
-        static const int per_cu = resident_per_cu(attn_bwd_dq_from_ds_kernel<D>, smem);
-        const QueueLaunch ql = tile_queue_prepare(a, items, a.Hq, per_cu, st);
+        const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st);
         if (ql.err != hipSuccess) return hip_fail(ql.err);
         attn_bwd_dq_from_ds_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
@@ -901,10 +908,11 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
       }
     }
     constexpr int smem = 2 * 2 * 64 * D * 2;
-    int rc = set_smem(attn_bwd_dq_kernel<D>, smem);
+    static KernelSetup setup;
+    int per_cu = 1;
+    int rc = kernel_setup(setup, attn_bwd_dq_kernel<D>, smem, &per_cu);
     if (rc) return rc;
-    static const int per_cu = resident_per_cu(attn_bwd_dq_kernel<D>, smem);
-    const QueueLaunch ql = tile_queue_prepare(a, items, a.Hq, per_cu, st);
+    const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st);
     if (ql.err != hipSuccess) return hip_fail(ql.err);
     attn_bwd_dq_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
@@ -913,15 +921,16 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
   auto dkdv_phase = [&](auto store_c) -> int {
     constexpr bool kStore = decltype(store_c)::value;
     constexpr int smem = DkdvCfg<D>::SMEM_BYTES;
-    int rc = set_smem(attn_bwd_dkdv_kernel<D, kStore>, smem);
+    static KernelSetup setup;
+    int per_cu = 1;
+    int rc = kernel_setup(setup, attn_bwd_dkdv_kernel<D, kStore>, smem, &per_cu);
     if (rc) return rc;
     int64_t tiles = tiles_per_head(p.S, 128, p.cu, p.num_docs);
     int64_t items = tiles * p.B * p.Hkv;
     if (items >= ((int64_t)1 << 31)) return kErrShape;
     AttnParams a = p;
     a.tiles = (int32_t)tiles;
-    static const int per_cu = resident_per_cu(attn_bwd_dkdv_kernel<D, kStore>, smem);
-    const QueueLaunch ql = tile_queue_prepare(a, items, a.Hkv, per_cu, st);
+    const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDkdv, items, a.Hkv, per_cu, st);
     if (ql.err != hipSuccess) return hip_fail(ql.err);
     attn_bwd_dkdv_kernel<D, kStore><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);

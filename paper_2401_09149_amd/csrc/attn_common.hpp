@@ -46,8 +46,10 @@ struct AttnParams {
   float scale, scale_log2;  // scale_log2 = scale * log2(e)
   int32_t causal;
   int32_t tiles;            // tiles per head the grid was sized for (upper bound when packed)
-  int32_t q_slot, q_per_xcd, q_total;  // persistent launches (tile_queue.hpp): counter slot, items per XCD list (0: one list), items
+  int32_t q_reserved, q_per_xcd, q_total;  // persistent launches (tile_queue.hpp): items per XCD list (0: one list), items
   __bf16* ds;               // optional workspace: dS written by the dK/dV kernel for the dQ kernel (see ds_matrix_offset), or NULL
+  unsigned int* q_counters;       // persistent launches: this launch's eight work-queue counters
+  unsigned int* ws_counters;      // backward: counter blocks in the caller's workspace (kQueueBytes each, one per kernel)
 };
 
 // Layout of the dS workspace (dense input, S a multiple of 128, head dimension 128): for every
@@ -411,7 +413,7 @@ struct TileCoord {
 // alternate (head = w % (B*H)).  `heavy_last` says whether high tile numbers carry the most work
 // (forward and dq: causal rows late in a document see more keys).
 template <int TS>
-__device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads, bool heavy_last, int* scratch, int w) {
+__device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads, bool heavy_last, int* scratch, int w, int tid) {
   TileCoord c;
   int nH = (int)p.B * heads;
   int hh, t;
@@ -437,7 +439,8 @@ __device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads,
   }
   // Packed: find the document whose tile range contains t.  Thread i counts the tiles of
   // documents i, i+256, ... in rounds of 256 documents with a block-wide scan per round.
-  int tid = threadIdx.x;
+  // (`tid` is the caller's copy of the thread index: persistent kernels pass an opaque one, so that nothing
+  // below is computed ahead of their item loop and kept in registers through it)
   int lane = tid & 63, wv = tid >> 6;
   int* s_wave = scratch;       // [4] wave totals
   int* s_res = scratch + 4;    // [0] doc index or -1, [1] tiles before that doc

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
 
-  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, blockIdx.x);
+  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, blockIdx.x, tid);
   if (!tc.valid) return;
   const int g = tc.h / (p.Hq / p.Hkv);
   const int64_t q0 = tc.t0;

@@ -22,6 +22,7 @@
 // pipeline never drains at a tile boundary; it is filled in a wave's first round and drained
 // after its last unmasked tile.  Tiles that need a mask for this wave (the diagonal, the end of
 // a document) take a compiler-scheduled path afterwards.
+#include <mutex>
 #include <type_traits>
 
 #include "attn_common.hpp"
@@ -59,7 +60,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int scratch[8];
 
-  __shared__ int s_work;
+  __shared__ QueueState s_work;
+  queue_init(p, &s_work);
   const uint32_t xcc = xcc_id();
   int skip = 0;
   for (;;) {   // persistent: one item (batch, head, query tile) per iteration
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
-  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item);
+  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item, tid);
   if (!tc.valid) continue;
   const int g = tc.h / (p.Hq / p.Hkv);
   const int64_t q0 = tc.t0;
@@ -510,18 +512,111 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   }  // next item
 }
 
+// ---- counter slots of the forward's work queue ------------------------------------------------
+// The forward has no workspace argument, so its launches take their eight queue counters from a pool
+// of slots in a file-scope device array.  A slot must belong to one launch at a time: the host records
+// an event behind every launch and hands a slot out again only when that event has completed, or to a
+// launch on the same stream (which runs after it anyway); a slot used under stream capture stays with
+// that graph for good (its replays are invisible to the host).  When every slot is in flight on other
+// streams or pinned, the call fails with IE_ERR_BUSY instead of sharing one.
+constexpr int kFwdSlots = 256;
+static __device__ __align__(256) unsigned int g_fwd_queue[kFwdSlots * (kQueueBytes / 4)];
+
+namespace {
+enum : unsigned char { kSlotFree = 0, kSlotPending = 1, kSlotPinned = 2, kSlotLaunching = 3 };
+struct SlotPool {
+  std::mutex mu;
+  unsigned int* base = nullptr;       // device address of g_fwd_queue on this device
+  hipEvent_t ev[kFwdSlots] = {};      // behind the slot's latest launch (created on first use)
+  hipStream_t stream[kFwdSlots] = {}; // the stream of that launch
+  unsigned char state[kFwdSlots] = {};
+  int next = 0;
+};
+SlotPool g_pools[kMaxDevices];
+
+// Returns 0 and a slot (index, device address of its counters), or a status.
+int slot_acquire(hipStream_t st, int* dev_out, int* slot_out, unsigned int** counters, bool* capturing) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev >= kMaxDevices) return kErrBusy;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if ((e = hipStreamIsCapturing(st, &cs)) != hipSuccess) return hip_fail(e);
+  *capturing = cs == hipStreamCaptureStatusActive;
+  SlotPool& pool = g_pools[dev];
+  std::lock_guard<std::mutex> lock(pool.mu);
+  if (pool.base == nullptr) {
+    void* ptr = nullptr;
+    if ((e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_fwd_queue))) != hipSuccess) return hip_fail(e);
+    pool.base = static_cast<unsigned int*>(ptr);
+  }
+  int found = -1;
+  for (int i = 0; i < kFwdSlots && found < 0; ++i) {
+    const int s = (pool.next + i) % kFwdSlots;
+    if (pool.state[s] == kSlotPending) {
+      const hipError_t q = hipEventQuery(pool.ev[s]);
+      if (q == hipSuccess) pool.state[s] = kSlotFree;
+      else (void)hipGetLastError();   // "not ready" must not be taken for a launch failure later on
+    }
+    if (pool.state[s] == kSlotFree) found = s;
+  }
+  // nothing has completed: a slot whose launch sits earlier on this very stream is as good
+  for (int i = 0; i < kFwdSlots && found < 0 && !*capturing; ++i) {
+    const int s = (pool.next + i) % kFwdSlots;
+    if (pool.state[s] == kSlotPending && pool.stream[s] == st) found = s;
+  }
+  if (found >= 0) {
+    pool.state[found] = kSlotLaunching;
+    pool.next = (found + 1) % kFwdSlots;
+    *dev_out = dev;
+    *slot_out = found;
+    *counters = pool.base + found * (kQueueBytes / 4);
+    return 0;
+  }
+  return kErrBusy;
+}
+
+// After the launch (or a failed attempt): ties the slot to what was enqueued.
+void slot_release(int dev, int slot, hipStream_t st, bool capturing, bool launched) {
+  SlotPool& pool = g_pools[dev];
+  std::lock_guard<std::mutex> lock(pool.mu);
+  if (!launched) { pool.state[slot] = kSlotFree; return; }
+  if (capturing) { pool.state[slot] = kSlotPinned; return; }
+  if (pool.ev[slot] == nullptr && hipEventCreateWithFlags(&pool.ev[slot], hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    pool.ev[slot] = nullptr;
+    pool.state[slot] = kSlotPinned;   // without an event the slot cannot be shown to be free again
+    return;
+  }
+  if (hipEventRecord(pool.ev[slot], st) != hipSuccess) {
+    (void)hipGetLastError();
+    pool.state[slot] = kSlotPinned;
+    return;
+  }
+  pool.stream[slot] = st;
+  pool.state[slot] = kSlotPending;
+}
+}  // namespace
+
 int launch_fwd_wide(AttnParams p, hipStream_t st) {
   constexpr int smem = FwdWideCfg::SMEM_BYTES;
-  int rc = set_smem(attn_fwd_wide_kernel, smem);
+  static KernelSetup setup;
+  int per_cu = 1;
+  int rc = kernel_setup(setup, attn_fwd_wide_kernel, smem, &per_cu);
   if (rc) return rc;
   int64_t tiles = tiles_per_head(p.S, FwdWideCfg::BM, p.cu, p.num_docs);
   int64_t items = tiles * p.B * p.Hq;
   if (items >= ((int64_t)1 << 31)) return kErrShape;
   p.tiles = (int32_t)tiles;
-  const QueueLaunch ql = tile_queue_prepare(p, items, p.Hq, 1, st);
-  if (ql.err != hipSuccess) return hip_fail(ql.err);
+  int dev = 0, slot = 0;
+  unsigned int* counters = nullptr;
+  bool capturing = false;
+  if ((rc = slot_acquire(st, &dev, &slot, &counters, &capturing)) != 0) return rc;
+  const QueueLaunch ql = tile_queue_prepare(p, counters, items, p.Hq, 1, st);
+  if (ql.err != hipSuccess) { slot_release(dev, slot, st, capturing, false); return hip_fail(ql.err); }
   attn_fwd_wide_kernel<<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
   hipError_t e = hipGetLastError();
+  slot_release(dev, slot, st, capturing, true);   // (the reset kernel is enqueued either way)
   return e == hipSuccess ? 0 : hip_fail(e);
 }
 

@@ -17,6 +17,10 @@ constexpr int64_t kMaxElems = (int64_t)1 << 40;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// One [B,Hq,S] fp32 plane of the backward workspace; and its counter area (tile_queue.hpp: 32 bytes per kernel).
+size_t stat_bytes(int64_t B, int64_t S, int32_t Hq) { return align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256); }
+constexpr size_t kCounterBytes = 256;
+
 ie::AttnParams base_params(const int32_t* cu, int32_t num_docs, int64_t B, int64_t S, int32_t Hq, int32_t Hkv,
                            float scale, int32_t causal) {
   ie::AttnParams p;
@@ -77,7 +81,8 @@ int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
 size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs) {
   (void)num_docs;
   if (check_shape(nullptr, 0, B, S, Hq, Hkv, D, 1.0f, 1) != IE_OK) return 0;
-  return 2 * align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256);  // delta and lse*log2e, [B,Hq,S] each
+  // -delta and -lse*log2e, [B,Hq,S] fp32 each, then the work-queue counters of the call's kernels
+  return 2 * stat_bytes(B, S, Hq) + kCounterBytes;
 }
 
 // dS of dense input, bf16 in 128 x 128 blocks: per (batch, query head) the lower block triangle when causal, else all.
@@ -110,9 +115,14 @@ int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* 
   if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return IE_ERR_NULL;
   int rc = check_shape(cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal);
   if (rc) return rc;
-  if (phases <= 0 || (phases & ~IE_BWD_ALL) != 0) return IE_ERR_UNSUPPORTED;
-  size_t need = ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs);
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < need) return IE_ERR_WORKSPACE;
+  if ((phases & IE_BWD_ALL) == 0 || (phases & ~(IE_BWD_ALL | IE_BWD_STORED_DS)) != 0) return IE_ERR_UNSUPPORTED;
+  const size_t need = ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs);
+  size_t required = need;
+  if (phases & IE_BWD_STORED_DS) {   // the caller asks for the path that keeps dS in the workspace
+    required = cu_seqlens ? need : ie_attn_bwd_fast_workspace_bytes(B, S, Hq, Hkv, D, 0, causal);
+    if (required == need) return IE_ERR_UNSUPPORTED;   // this shape has no such path
+  }
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < required) return IE_ERR_WORKSPACE;
   ie::AttnParams p = base_params(cu_seqlens, num_docs, B, S, Hq, Hkv, scale, causal);
   p.q = static_cast<const __bf16*>(q);
   p.k = static_cast<const __bf16*>(k);
@@ -120,16 +130,16 @@ int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* 
   p.o = static_cast<const __bf16*>(o);
   p.dout = static_cast<const __bf16*>(dout);
   p.lse = lse;
-  p.delta = static_cast<float*>(workspace);
-  p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 2);
-  // A workspace with room for dS selects the path that stores it (only dense causal input has one).
-  const size_t fast = cu_seqlens ? need : ie_attn_bwd_fast_workspace_bytes(B, S, Hq, Hkv, D, 0, causal);
-  p.ds = (fast > need && workspace_bytes >= fast) ? reinterpret_cast<__bf16*>(static_cast<char*>(workspace) + need) : nullptr;
+  char* ws = static_cast<char*>(workspace);
+  p.delta = reinterpret_cast<float*>(ws);
+  p.lse2 = reinterpret_cast<float*>(ws + stat_bytes(B, S, Hq));
+  p.ws_counters = reinterpret_cast<unsigned int*>(ws + 2 * stat_bytes(B, S, Hq));
+  p.ds = (phases & IE_BWD_STORED_DS) ? reinterpret_cast<__bf16*>(ws + need) : nullptr;
   p.dq = static_cast<__bf16*>(dq);
   p.dk = static_cast<__bf16*>(dk);
   p.dv = static_cast<__bf16*>(dv);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  return ie::launch_bwd(p, D, phases, st);
+  return ie::launch_bwd(p, D, phases & IE_BWD_ALL, st);
 }
 
 const char* ie_attn_strerror(int code) {
@@ -137,10 +147,11 @@ const char* ie_attn_strerror(int code) {
     case IE_OK: return "success";
     case IE_ERR_NULL: return "a required pointer is NULL";
     case IE_ERR_SHAPE: return "invalid shape (sizes must be positive, Hq % Hkv == 0, packed input needs B == 1 and num_docs >= 1)";
-    case IE_ERR_UNSUPPORTED: return "unsupported configuration (D must be 64 or 128, scale finite and > 0, causal 0 or 1)";
+    case IE_ERR_UNSUPPORTED: return "unsupported configuration (D must be 64 or 128, scale finite and > 0, causal 0 or 1; phase and path flags valid for the shape)";
     case IE_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case IE_ERR_HIP: return "a HIP runtime call failed";
     case IE_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    case IE_ERR_BUSY: return "every work-queue slot of the forward kernel is in flight or held by a captured graph";
     default: return "unknown ie_attn status";
   }
 }

@@ -17,17 +17,19 @@ int launch_fwd_wide(AttnParams p, hipStream_t st);  // head dimension 128
 // phases: bit 0 delta, bit 1 dq, bit 2 dk/dv
 int launch_bwd(AttnParams p, int D, int phases, hipStream_t st);
 
+constexpr int kMaxDevices = 64;   // per-device host state is kept for device ordinals below this
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Compute units of the current device (cached per device); 0 and *err set if the runtime refuses.
 inline int cu_count(hipError_t* err) {
-  static std::atomic<int> cus_of[64];
+  static std::atomic<int> cus_of[kMaxDevices];
   int dev = 0;
   if ((*err = hipGetDevice(&dev)) != hipSuccess) return 0;
-  int cus = dev < 64 ? cus_of[dev].load(std::memory_order_relaxed) : 0;
+  int cus = dev < kMaxDevices ? cus_of[dev].load(std::memory_order_relaxed) : 0;
   if (cus == 0) {
     if ((*err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return 0;
-    if (dev < 64) cus_of[dev].store(cus, std::memory_order_relaxed);
+    if (dev < kMaxDevices) cus_of[dev].store(cus, std::memory_order_relaxed);
   }
   return cus;
 }
@@ -39,6 +41,7 @@ inline int64_t tiles_per_head(int64_t S, int64_t ts, const int32_t* cu, int32_t 
 }
 
 constexpr int kErrShape = -2;  // IE_ERR_SHAPE
+constexpr int kErrBusy = -7;   // IE_ERR_BUSY
 
 template <typename K>
 inline int set_smem(K kernel, int bytes) {

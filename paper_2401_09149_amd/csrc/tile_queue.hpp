@@ -10,10 +10,10 @@
 // that the workgroups of an XCD still stream the same head's K/V through its L2 together), and a
 // workgroup whose list is empty takes from the next XCD's list.
 //
-// The counters live in a file-scope device array (one copy per translation unit that includes
-// this header, and per device); a launch uses one slot of it, cleared by a one-wave kernel on
-// the same stream in front of the main kernel.  Slots rotate per launch, so launches that overlap
-// on different streams do not share a slot unless kQueueSlots of them are in flight at once.
+// The eight counters of a launch (32 bytes, `AttnParams::q_counters`) are memory that belongs to
+// that launch alone: the backward kernels take them from the caller's workspace, the forward from
+// a pool of slots whose use the host tracks with events (attn_fwd_wide.hip).  A one-wave kernel on
+// the same stream clears them in front of the main kernel.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -24,12 +24,10 @@
 
 namespace ie {
 
-constexpr int kQueueSlots = 256;
-struct TileQueue { unsigned int next[8]; };
-static __device__ TileQueue g_tile_queue[kQueueSlots];
+constexpr int kQueueBytes = 32;   // 8 counters
 
-static __global__ void tile_queue_reset_kernel(int slot) {
-  if (threadIdx.x < 8) g_tile_queue[slot].next[threadIdx.x] = 0u;
+static __global__ void tile_queue_reset_kernel(unsigned int* counters) {
+  if (threadIdx.x < 8) counters[threadIdx.x] = 0u;
 }
 
 // The XCD this wave runs on (0..7).
@@ -43,11 +41,18 @@ __device__ __forceinline__ uint32_t xcc_id() {
 // threads of the workgroup call it; it contains two barriers, so on return everyone has left the
 // previous item (its LDS is free) and sees the same result.  `skip` (per workgroup, starts at 0)
 // remembers how many lists were already found empty.
-__device__ __forceinline__ int next_work(const AttnParams& p, int* s_work, uint32_t xcc, int& skip) {
+// `s_work` points at the workgroup's queue state in LDS, which queue_init() has set up.
+struct QueueState { unsigned int* counters; int work; };
+__device__ __forceinline__ void queue_init(const AttnParams& p, QueueState* s) {
+  // (the counters' address is parked in LDS: held in scalar registers through an item's main loop it would
+  // cost the one-wave-per-SIMD kernels registers they do not have)
+  if (threadIdx.x == 0) s->counters = p.q_counters;
+}
+__device__ __forceinline__ int next_work(const AttnParams& p, QueueState* s_work, uint32_t xcc, int& skip) {
   __syncthreads();
   if (threadIdx.x == 0) {
     int w = -1;
-    unsigned int* next = g_tile_queue[p.q_slot].next;
+    unsigned int* next = s_work->counters;
     if (p.q_per_xcd > 0) {
       for (; skip < 8; ++skip) {
         const uint32_t x = (xcc + (uint32_t)skip) & 7u;
@@ -58,37 +63,46 @@ __device__ __forceinline__ int next_work(const AttnParams& p, int* s_work, uint3
       const unsigned int s = atomicAdd(next, 1u);
       if (s < (unsigned int)p.q_total) w = (int)s;
     }
-    *s_work = w;
+    s_work->work = w;
   }
   __syncthreads();
-  return (int)uniform((uint32_t)*s_work);
+  return (int)uniform((uint32_t)s_work->work);
 }
 
-// Workgroups of `kernel` that fit on one CU together (registers, LDS); at least 1.
+// Per kernel and device: the dynamic LDS limit is raised once, and the number of workgroups of `kernel`
+// that fit on one CU together (registers, LDS; at least 1) is asked once.
+struct KernelSetup { std::atomic<int> per_cu[kMaxDevices]; };
 template <typename K>
-static inline int resident_per_cu(K kernel, int smem_bytes) {
-  int n = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(kernel), kThreads, (size_t)smem_bytes) != hipSuccess) n = 1;
-  return n < 1 ? 1 : n;
+static inline int kernel_setup(KernelSetup& ks, K kernel, int smem_bytes, int* per_cu) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  int n = dev < kMaxDevices ? ks.per_cu[dev].load(std::memory_order_acquire) : 0;
+  if (n == 0) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes);
+    if (e != hipSuccess) return hip_fail(e);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(kernel), kThreads, (size_t)smem_bytes) != hipSuccess || n < 1) n = 1;
+    if (dev < kMaxDevices) ks.per_cu[dev].store(n, std::memory_order_release);
+  }
+  *per_cu = n;
+  return 0;
 }
 
-// Host side: fills the queue fields of `p` for `total` items (= tiles per head x B x heads) and
-// clears the slot on `st`.  Returns the grid size for `per_cu` resident workgroups per CU.
-// (static: every translation unit that includes this header has its own counter array and reset kernel,
-// and must call its own copy of this function; a shared inline copy would clear one unit's array for all.)
+// Host side: fills the queue fields of `p` for `total` items (= tiles per head x B x heads) with the
+// launch's own `counters` (device memory, 32 bytes) and clears them on `st`.  Returns the grid size for
+// `per_cu` resident workgroups per CU.
 struct QueueLaunch { int grid; hipError_t err; };
-static inline QueueLaunch tile_queue_prepare(AttnParams& p, int64_t total, int heads, int per_cu, hipStream_t st) {
-  static std::atomic<unsigned int> next_slot{0};
+static inline QueueLaunch tile_queue_prepare(AttnParams& p, unsigned int* counters, int64_t total, int heads, int per_cu, hipStream_t st) {
   QueueLaunch r{0, hipSuccess};
   const int cus = cu_count(&r.err);
   if (r.err != hipSuccess) return r;
   const int64_t nH = p.B * heads;
-  p.q_slot = (int32_t)(next_slot.fetch_add(1u, std::memory_order_relaxed) % kQueueSlots);
+  p.q_counters = counters;
   p.q_total = (int32_t)total;
   p.q_per_xcd = (nH % 8 == 0) ? (int32_t)(total / 8) : 0;
   const int64_t want = (int64_t)cus * per_cu;
   r.grid = (int)(total < want ? total : want);
-  tile_queue_reset_kernel<<<1, 64, 0, st>>>(p.q_slot);
+  tile_queue_reset_kernel<<<1, 64, 0, st>>>(counters);
   r.err = hipGetLastError();
   return r;
 }

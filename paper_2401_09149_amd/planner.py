@@ -89,9 +89,11 @@ def violated_constraints(plan, model, N, B_tokens, S):
     return bad
 
 
-def memory_bytes(plan, model, S, other_bytes=0.0):
+def memory_bytes(plan, model, S, other_bytes=0.0, compute=None):
     """GPU memory of the Transformer layers (Sec. 3.2) plus `other_bytes` (head, embedding, buffers: profiled in
-    the paper, a parameter here).  Returns the parts and their total."""
+    the paper, a parameter here) plus the workspace of the attention backward path whose time `compute` reports
+    (one layer's worth: it is live during one layer's backward pass and shared by all layers).  Returns the parts
+    and their total."""
     p = plan
     states = model.L * model.psi / (p.s_pp * p.s_tp)          # parameters held per GPU before sharding
     P = 2.0 * states / p.s_ps
@@ -99,7 +101,11 @@ def memory_bytes(plan, model, S, other_bytes=0.0):
     OS = 6.0 * states / (p.s_ps * p.s_oss)
     per_layer = p.b * S * model.H * (2 + 32 * (1 - p.a))       # bytes, one micro-batch, one layer
     ACT = min(p.s_pp, p.n) * model.L * per_layer / (p.s_pp * p.s_sp)
-    return {"P": P, "G": G, "OS": OS, "ACT": ACT, "other": float(other_bytes), "total": P + G + OS + ACT + other_bytes}
+    ws = 0.0
+    if compute is not None and hasattr(compute, "attention_workspace_bytes"):
+        ws = float(compute.attention_workspace_bytes(p.b, S, max(1, model.heads // max(p.s_sp, p.s_tp))))
+    return {"P": P, "G": G, "OS": OS, "ACT": ACT, "other": float(other_bytes), "attn_workspace": ws,
+            "total": P + G + OS + ACT + other_bytes + ws}
 
 
 class SyntheticBandwidth:
@@ -165,20 +171,35 @@ class ProfiledCompute(AnalyticCompute):
     simulator looks the times up): `table` is the JSON that `self_atten_sweep --json` writes.  A shape that was
     measured is looked up; any other falls back to the measured shape with the nearest FLOP count, scaled by the ratio
     of FLOP counts (attention time is proportional to b * heads * S^2 once the chip is full).  The linear modules stay
-    analytic.  `stored_ds`: use the backward time of the path that stores dS where the table has one."""
+    analytic.  `stored_ds`: use the backward time of the path that keeps dS in a workspace of b * heads * S * (S + 128)
+    bytes where the table has one; `attention_workspace_bytes` then reports those bytes and `memory_bytes` charges them.
+    Off by default: the fused kernel is in the paper's design because it keeps attention memory O(S) (Sec. 3.2)."""
 
-    def __init__(self, table, linear_flops=1.15e15, stored_ds=True):
+    def __init__(self, table, linear_flops=1.15e15, stored_ds=False):
         super().__init__(linear_flops=linear_flops)
         import json
         if isinstance(table, str):
             with open(table) as f:
                 table = json.load(f)
-        self.records = {}
+        self.records, self.stored = {}, {}
         for r in table["records"]:
-            bwd = r["bwd_stored_ds_ms"] if stored_ds and r.get("bwd_stored_ds_ms") else r["bwd_ms"]
+            use_ds = bool(stored_ds and r.get("bwd_stored_ds_ms"))
+            bwd = r["bwd_stored_ds_ms"] if use_ds else r["bwd_ms"]
             self.records[(r["b"], r["S"], r["heads"])] = (r["fwd_ms"] * 1e-3, bwd * 1e-3)
+            self.stored[(r["b"], r["S"], r["heads"])] = use_ds
         if not self.records:
             raise ValueError("empty attention table")
+
+    def _nearest(self, b, S, heads):
+        want = float(b) * heads * S * S
+        return min(self.records, key=lambda k: abs(math.log(want / (float(k[0]) * k[2] * k[1] * k[1]))))
+
+    def attention_workspace_bytes(self, b, S, heads):
+        """Bytes of backward workspace behind the time attention_times reports: two [b, heads, S] fp32 planes, plus
+        dS (bf16, the lower block triangle: b * heads * S * (S + 128) bytes) where the stored-dS time is used."""
+        key = (b, S, heads) if (b, S, heads) in self.records else self._nearest(b, S, heads)
+        small = 8.0 * b * heads * S
+        return small + (float(b) * heads * S * (S + 128) if self.stored[key] else 0.0)
 
     def attention_times(self, b, S, heads):
         """(forward, backward) seconds of self-atten(b, S, heads) on one GPU."""
@@ -186,7 +207,7 @@ class ProfiledCompute(AnalyticCompute):
         if hit:
             return hit
         want = float(b) * heads * S * S
-        key = min(self.records, key=lambda k: abs(math.log(want / (float(k[0]) * k[2] * k[1] * k[1]))))
+        key = self._nearest(b, S, heads)
         f, bw_ = self.records[key]
         ratio = want / (float(key[0]) * key[2] * key[1] * key[1])
         return f * ratio, bw_ * ratio
@@ -248,7 +269,7 @@ def search(model, S, N, B_tokens, capacity_bytes, bw=None, compute=None, top=10,
             continue
         if violated_constraints(plan, model, N, B_tokens, S):
             continue
-        if memory_bytes(plan, model, S, other_bytes)["total"] > capacity_bytes:
+        if memory_bytes(plan, model, S, other_bytes, compute)["total"] > capacity_bytes:
             continue
         t = step_time(plan, model, S, N, bw, compute, R)
         if len(best) < top:

@@ -64,6 +64,8 @@ def main():
         ws = binding.alloc_bwd_workspace(q, k, None)
         fwd = lambda: binding.ie_attn_fwd(q, k, v, o, lse, None, scale, True)
         bwd = lambda: binding.ie_attn_bwd_phases(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws, binding.BWD_ALL)
+        bwd_ds = lambda: binding.ie_attn_bwd_phases(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws, binding.BWD_ALL,
+                                                    stored_ds=True)
 
         def timed(fn):
             for _ in range(2):
@@ -82,7 +84,7 @@ def main():
         if ws.numel() < big <= args.ds_limit_gb * 1e9:
             del ws
             ws = torch.empty(big, dtype=torch.uint8, device=dev)
-            s_ms = timed(bwd)
+            s_ms = timed(bwd_ds)
         flop_f = 2.0 * b * H * float(S) ** 2 * D   # 4 S^2 D H / 2 (causal halving); backward = 2.5x
         tf_f, tf_b = flop_f / f_ms / 1e9, 2.5 * flop_f / b_ms / 1e9
         both = 3.5 * flop_f / (f_ms + min(b_ms, s_ms or b_ms)) / 1e9

@@ -37,11 +37,11 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_strerror_is_total(lib):
     seen = set()
-    for code in range(-7, 2):
+    for code in range(-8, 2):
         s = lib.ie_attn_strerror(code)
         assert s and len(s) > 0
         seen.add(s)
-    assert len(seen) >= 8   # seven statuses + "unknown"
+    assert len(seen) >= 9   # eight statuses + "unknown"
 
 
 def test_workspace_query(lib):
@@ -89,6 +89,17 @@ def test_bad_arguments_fail_before_any_launch(lib):
     assert bwd(dq=None) == -1
     assert bwd(ws=None) == -4 and bwd(ws_bytes=16) == -4 and bwd(ws=ctypes.c_void_p(264)) == -4
     assert bwd(D=32) == -3
+
+    def phases(mask, ws_bytes=1 << 30, **kw):
+        a = dict(args, **kw)
+        return lib.ie_attn_bwd_phases(one, one, one, one, one, one, one, one, one, None, 0, a["B"], a["S"], a["Hq"], a["Hkv"],
+                                      a["D"], a["scale"], a["causal"], one, ws_bytes, mask, None)
+
+    assert phases(0) == -3 and phases(8) == -3 and phases(16) == -3 and phases(7 | 32) == -3   # no phase / unknown bits
+    assert phases(7 | 16, S=100) == -3                  # the stored-dS path does not exist for this shape
+    small = lib.ie_attn_bwd_workspace_bytes(1, 128, 4, 2, 128, 0)
+    assert phases(7 | 16, ws_bytes=small) == -4         # it exists, but the workspace has no room for dS
+
 
 
 def test_permute_bad_arguments_fail_before_any_launch(lib):

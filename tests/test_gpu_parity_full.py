@@ -21,7 +21,7 @@ def w64(t):
 
 
 def run_full(cfg, stored_ds=False):
-    """stored_ds: the backward path bench.py times where the shape has it (a workspace with room for dS)."""
+    """stored_ds: the optional backward path that keeps dS in the workspace (the shapes that have it)."""
     from paper_2401_09149_amd import binding, workloads as W
     cu = W.make_cu_seqlens(cfg)
     q, k, v, do = W.make_inputs(cfg)
@@ -32,7 +32,7 @@ def run_full(cfg, stored_ds=False):
     ws = binding.alloc_bwd_workspace(qd, kd, cud, fast=stored_ds, causal=cfg.causal)
     if stored_ds:
         assert ws.numel() > binding.alloc_bwd_workspace(qd, kd, cud).numel()
-    dq, dk, dv = binding.attn_bwd(qd, kd, vd, o, dod, lse, cfg.scale, cfg.causal, cud, workspace=ws)
+    dq, dk, dv = binding.attn_bwd(qd, kd, vd, o, dod, lse, cfg.scale, cfg.causal, cud, workspace=ws, stored_ds=stored_ds)
     torch.cuda.synchronize()
     del ws
     return cu, (q, k, v, do), (qd, kd, vd, dod), (o, lse, dq, dk, dv)

@@ -151,9 +151,10 @@ def test_backward_is_bitwise_reproducible_and_phases_compose():
 
 
 def test_overlapping_launches_on_two_streams_and_many_launches_in_a_row():
-    """The persistent kernels draw their items from per-launch counters that rotate through a fixed number
-    of slots: launches that overlap on two streams must not disturb each other, and the slots must come
-    back clean after a full rotation (more launches than slots)."""
+    """The persistent kernels draw their items from per-launch counters (backward: in the caller's workspace;
+    forward: one of a fixed number of slots, handed out again when its last launch has completed or sits on
+    the same stream): launches that overlap on two streams must not disturb each other, and many more launches
+    than slots in a row on one stream, with nothing completed in between, must all give the right result."""
     import torch
     from paper_2401_09149_amd import binding
     dev = "cuda:0"
@@ -183,7 +184,7 @@ def test_overlapping_launches_on_two_streams_and_many_launches_in_a_row():
     o3, lse3 = torch.empty_like(o), torch.empty_like(lse)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     ws = binding.alloc_bwd_workspace(q, k, None)
-    for _ in range(300):   # forward and backward kernels keep their counters in separate arrays: rotate both
+    for _ in range(300):   # more forward launches in flight than the pool has slots
         binding.ie_attn_fwd(q, k, v, o3, lse3, None, scale, True)
         binding.ie_attn_bwd(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws)
     for t in (o3, lse3, dq, dk, dv):
@@ -250,7 +251,7 @@ def test_forward_and_backward_can_be_captured_in_a_graph_and_replayed():
 
         def step():
             binding.ie_attn_fwd(q, k, v, o, lse, None, scale, True)
-            binding.ie_attn_bwd(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws)
+            binding.ie_attn_bwd(q, k, v, o, do, lse, dq, dk, dv, None, scale, True, ws, stored_ds=fast)
 
         step()   # eager once: one-time set-up (occupancy queries) happens outside the capture
         torch.cuda.synchronize()

@@ -56,7 +56,7 @@ def test_random_shape(oracle, case):
         dev = "cuda:0"
         qd, kd, vd, dod = (x.to(dev) for x in (q, k, v, do))
         ws = binding.alloc_bwd_workspace(qd, kd, None, fast=True, causal=causal)
-        stored = binding.attn_bwd(qd, kd, vd, got[0], dod, got[1], scale, causal, None, workspace=ws)
+        stored = binding.attn_bwd(qd, kd, vd, got[0], dod, got[1], scale, causal, None, workspace=ws, stored_ds=True)
         torch.cuda.synchronize()
         compare_all(got[:2] + tuple(stored), ref, f"random {i}, stored dS")
         assert torch.equal(stored[1], got[3]) and torch.equal(stored[2], got[4])

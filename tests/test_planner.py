@@ -166,9 +166,9 @@ def test_profiled_compute_looks_up_and_scales():
         {"b": 1, "S": 32768, "heads": 8, "fwd_ms": 2.0, "bwd_ms": 6.0, "bwd_stored_ds_ms": 5.0},
         {"b": 1, "S": 65536, "heads": 4, "fwd_ms": 4.0, "bwd_ms": 12.0, "bwd_stored_ds_ms": None},
     ]}
-    pc = pl.ProfiledCompute(table)
+    assert pl.ProfiledCompute(table).attention_times(1, 32768, 8) == (2.0e-3, 6.0e-3)   # default: the O(S) path
+    pc = pl.ProfiledCompute(table, stored_ds=True)
     assert pc.attention_times(1, 32768, 8) == (2.0e-3, 5.0e-3)
-    assert pl.ProfiledCompute(table, stored_ds=False).attention_times(1, 32768, 8) == (2.0e-3, 6.0e-3)
     assert pc.attention_times(1, 65536, 4) == (4.0e-3, 12.0e-3)          # no stored-dS time: the recomputing one
     f, b = pc.attention_times(1, 32768, 10)                               # 1.25 times the work of the first record
     assert abs(f - 2.5e-3) < 1e-12 and abs(b - 6.25e-3) < 1e-12
@@ -178,6 +178,13 @@ def test_profiled_compute_looks_up_and_scales():
     assert abs(pc.layer_time(m, plan, 32768) - (2.0e-3 + 5.0e-3 + 3 * lin)) < 1e-12
     plan_a = pl.Plan(b=1, n=1, a=1, s_pp=1, s_dp=1, s_tp=1, s_sp=4, s_ps=1, s_gs=1, s_oss=1)
     assert abs(pc.layer_time(m, plan_a, 32768) - (2 * (2.0e-3 + lin) + 5.0e-3 + 2 * lin)) < 1e-12
+    # the stored-dS time comes with its memory: the workspace is charged to the plan
+    assert pc.attention_workspace_bytes(1, 32768, 8) == 8 * 8 * 32768 + 8 * 32768 * (32768 + 128)
+    assert pc.attention_workspace_bytes(1, 65536, 4) == 8 * 4 * 65536                   # no stored-dS time in the table
+    assert pl.ProfiledCompute(table).attention_workspace_bytes(1, 32768, 8) == 8 * 8 * 32768
+    mem = pl.memory_bytes(plan, m, 32768, compute=pc)
+    assert mem["attn_workspace"] == pc.attention_workspace_bytes(1, 32768, 8)
+    assert mem["total"] == pl.memory_bytes(plan, m, 32768)["total"] + mem["attn_workspace"]
     # usable by the search in place of the analytic model
     best = pl.search(m, 32768, 32, 4 * 2 ** 20, 80e9, compute=pc, top=3)
     assert best and all(t > 0 for t, _ in best)
