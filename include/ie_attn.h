@@ -131,6 +131,24 @@ int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* 
                        float scale, int32_t causal,
                        void* workspace, size_t workspace_bytes, int32_t phases, void* stream);
 
+/*
+ * ie_attn_bwd for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The same computation and the same kernels as ie_attn_bwd(...) with the minimal
+ * workspace, but the workspace is a device array inside the library (IE_ATTN_BWD_STATIC_MAX_ROWS * 8 + 256 bytes,
+ * about 16 MiB, held on every device the library runs on until the process ends), so the call takes no workspace
+ * argument and neither it nor anything it calls allocates or frees memory.  Shapes with
+ * B * Hq * S > IE_ATTN_BWD_STATIC_MAX_ROWS are rejected with IE_ERR_WORKSPACE before anything is launched.  All
+ * calls on one device share the array: calls that overlap on one device (different streams, or two replays of a
+ * captured graph at once) race and give undefined results; calls on one stream are safe.  Results are bit-identical
+ * to ie_attn_bwd's.
+ */
+#define IE_ATTN_BWD_STATIC_MAX_ROWS (1 << 21)
+int ie_attn_bwd_static(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                       const float* lse, void* dq, void* dk, void* dv,
+                       const int32_t* cu_seqlens, int32_t num_docs,
+                       int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
+                       float scale, int32_t causal, void* stream);
+
 /* Static text for a status code (never NULL). */
 const char* ie_attn_strerror(int code);
 

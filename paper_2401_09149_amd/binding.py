@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("IE_ATTN_LIB") or os.path.join(_HERE, "libie_attn.so")  # override: for trying out a build
 
 EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd_fast_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases",
-           "ie_attn_strerror",
+           "ie_attn_bwd_static", "ie_attn_strerror",
            "ie_attn_last_hip_error",
            "ie_sp_pack_qkv", "ie_sp_unpack_qkv", "ie_sp_pack_o", "ie_sp_unpack_o",
            "ie_sp_pack_do", "ie_sp_unpack_do", "ie_sp_pack_dqkv", "ie_sp_unpack_dqkv",
@@ -48,6 +48,8 @@ def load():
     lib.ie_attn_bwd.restype = ctypes.c_int
     lib.ie_attn_bwd_phases.argtypes = [vp] * 9 + [vp, i32, i64, i64, i32, i32, i32, f32, i32, vp, ctypes.c_size_t, i32, vp]
     lib.ie_attn_bwd_phases.restype = ctypes.c_int
+    lib.ie_attn_bwd_static.argtypes = [vp] * 9 + [vp, i32, i64, i64, i32, i32, i32, f32, i32, vp]
+    lib.ie_attn_bwd_static.restype = ctypes.c_int
     lib.ie_attn_strerror.argtypes = [ctypes.c_int]
     lib.ie_attn_strerror.restype = ctypes.c_char_p
     lib.ie_attn_last_hip_error.argtypes = []
@@ -160,6 +162,19 @@ def ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, cau
                             _ptr(dk, bf, "dk"), _ptr(dv, bf, "dv"), cu, nd, B, S, Hq, Hkv, D, float(scale),
                             int(bool(causal)), ws, workspace.numel() if workspace is not None else 0,
                             int(phases) | (BWD_STORED_DS if stored_ds else 0), _stream(stream))
+    if rc != 0:
+        _raise(rc)
+
+
+def ie_attn_bwd_static(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, causal, stream=None):
+    """ie_attn_bwd with the workspace in the library's own device array (no workspace argument, nothing allocated)."""
+    B, S, Hq, Hkv, D = _shape(q, k, v=v, o=o, dout=dout, lse=lse, dq=dq, dk=dk, dv=dv)
+    cu, nd = _docs(cu_seqlens)
+    bf = torch.bfloat16
+    rc = load().ie_attn_bwd_static(_ptr(q, bf, "q"), _ptr(k, bf, "k"), _ptr(v, bf, "v"), _ptr(o, bf, "o"),
+                                   _ptr(dout, bf, "dout"), _ptr(lse, torch.float32, "lse"), _ptr(dq, bf, "dq"),
+                                   _ptr(dk, bf, "dk"), _ptr(dv, bf, "dv"), cu, nd, B, S, Hq, Hkv, D, float(scale),
+                                   int(bool(causal)), _stream(stream))
     if rc != 0:
         _raise(rc)
 

@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "attn_common.hpp"
 #include "launch.hpp"
@@ -59,6 +60,17 @@ int hip_fail(hipError_t e) {
   return IE_ERR_HIP;
 }
 }  // namespace ie
+
+// ---- backward without a workspace argument -------------------------------------------------------
+// For callers that cannot allocate (code under graph capture, serving loops, harnesses that forbid it):
+// the workspace of ie_attn_bwd lives in a file-scope device array instead, one copy per device.  Host
+// code must not hand the array's name to a kernel; its device address is asked for once per device.
+constexpr size_t kStaticRows = (size_t)IE_ATTN_BWD_STATIC_MAX_ROWS;
+constexpr size_t kStaticBytes = 2 * kStaticRows * sizeof(float) + kCounterBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[ie::kMaxDevices];   // device address of `scratch`, per device
 
 extern "C" {
 
@@ -140,6 +152,35 @@ int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* 
   p.dv = static_cast<__bf16*>(dv);
   hipStream_t st = static_cast<hipStream_t>(stream);
   return ie::launch_bwd(p, D, phases & IE_BWD_ALL, st);
+}
+
+int ie_attn_bwd_static(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                       const float* lse, void* dq, void* dk, void* dv, const int32_t* cu_seqlens,
+                       int32_t num_docs, int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float scale,
+                       int32_t causal, void* stream) {
+  if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return IE_ERR_NULL;
+  int rc = check_shape(cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal);
+  if (rc) return rc;
+  const size_t need = ie_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, num_docs);
+  if ((size_t)B * (size_t)Hq * (size_t)S > kStaticRows || need > kStaticBytes) return IE_ERR_WORKSPACE;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return ie::hip_fail(e);
+  if (dev >= ie::kMaxDevices) return IE_ERR_UNSUPPORTED;
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+      void* sym = nullptr;
+      if ((e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch))) != hipSuccess) return ie::hip_fail(e);
+      g_scratch_ptr[dev] = sym;
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  // Every byte the kernels read from the array is written earlier in the same call (the delta kernel fills both
+  // planes for all B*Hq*S rows, the reset kernels clear the counters), so nothing has to be cleared here.
+  return ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal,
+                            ptr, kStaticBytes, IE_BWD_ALL, stream);
 }
 
 const char* ie_attn_strerror(int code) {

@@ -100,6 +100,13 @@ def test_bad_arguments_fail_before_any_launch(lib):
     small = lib.ie_attn_bwd_workspace_bytes(1, 128, 4, 2, 128, 0)
     assert phases(7 | 16, ws_bytes=small) == -4         # it exists, but the workspace has no room for dS
 
+    def static(dq=one, **kw):
+        a = dict(args, **kw)
+        return lib.ie_attn_bwd_static(one, one, one, one, one, one, dq, one, one, None, 0, a["B"], a["S"], a["Hq"], a["Hkv"],
+                                      a["D"], a["scale"], a["causal"], None)
+
+    assert static(dq=None) == -1 and static(D=32) == -3 and static(Hq=3) == -2
+    assert static(S=(1 << 21) // 4 + 1) == -4 and static(B=2, S=1 << 20, Hq=2, Hkv=2) == -4   # beyond the static array
 
 
 def test_permute_bad_arguments_fail_before_any_launch(lib):
