@@ -24,39 +24,57 @@
 namespace ie {
 
 // ---- delta = rowsum(dO o O) ------------------------------------------------------------
-// One (batch, token, head) row of D bf16 per group of D/8 lanes; rows are walked so that
-// consecutive groups take consecutive tokens of one head, which makes the [B,Hq,S]
-// writes contiguous while every read is a full row (D*2 contiguous bytes).  The same pass
-// stores lse * log2(e) next to delta.  Both are stored NEGATED: -delta is the C operand of the
-// first MFMA of every dP chain, which then delivers dP - delta directly, and -lse*log2(e) is the
-// addend of the fused multiply-add in front of each exp2.
+// HBM-bound: o and dO are read once, 2 * T * Hq * D * 2 bytes.  A workgroup takes kDeltaTokens consecutive
+// tokens of one batch entry with ALL their heads, which is one contiguous piece of o and of dO (the layout is
+// [B, S, Hq, D]), and walks it front to back with D/8 lanes per (token, head) row and eight rows per thread in
+// flight.  The sums are parked in LDS as [head][token] and written out from there, so that the [B, Hq, S]
+// planes receive runs of kDeltaTokens consecutive floats.  The same pass stores lse * log2(e) next to delta.
+// Both are stored NEGATED: -delta is the C operand of the first MFMA of every dP chain, which then delivers
+// dP - delta directly, and -lse*log2(e) is the addend of the fused multiply-add in front of each exp2.
+constexpr int kDeltaTokens = 32;   // per workgroup; fewer (p.tiles) when Hq * 32 floats would not fit the default LDS limit
 template <int D>
 __global__ __launch_bounds__(kThreads) void attn_bwd_delta_kernel(AttnParams p) {
   constexpr int LPR = D / 8;               // lanes per row
-  constexpr int RPB = kThreads / LPR;      // rows per pass of the workgroup
-  constexpr int PASSES = 8;
+  constexpr int RPP = kThreads / LPR;      // rows per pass of the workgroup
+  constexpr int UNROLL = 8;
+  extern __shared__ float s_delta[];       // [Hq][tokens per workgroup]
+  const int kTok = p.tiles;                // tokens per workgroup
   const int tid = threadIdx.x;
   const int sub = tid % LPR, rloc = tid / LPR;
-  const int64_t blocks_per_head = (p.S + RPB * PASSES - 1) / (RPB * PASSES);
-  const int64_t hh = blockIdx.x / blocks_per_head;  // b * Hq + h
-  const int64_t blk = blockIdx.x % blocks_per_head;
-  const int64_t b = hh / p.Hq, h = hh % p.Hq;
+  const int64_t blocks_per_batch = (p.S + kTok - 1) / kTok;
+  const int64_t b = blockIdx.x / blocks_per_batch;
+  const int64_t t0 = (blockIdx.x % blocks_per_batch) * kTok;
+  const int ntok = (int)(p.S - t0 < kTok ? p.S - t0 : kTok);
+  const int rows = ntok * p.Hq;            // (token, head) rows of this workgroup, contiguous in memory
+  const __bf16* o = p.o + (b * p.S + t0) * p.Hq * D;
+  const __bf16* dout = p.dout + (b * p.S + t0) * p.Hq * D;
+  for (int r0 = 0; r0 < rows; r0 += RPP * UNROLL) {
+    bf16x8 x[UNROLL], y[UNROLL];
 #pragma unroll
-  for (int ps = 0; ps < PASSES; ++ps) {
-    const int64_t i = (blk * PASSES + ps) * RPB + rloc;
-    float acc = 0.f;
-    if (i < p.S) {
-      const int64_t off = ((b * p.S + i) * p.Hq + h) * D + sub * 8;
-      bf16x8 x = *reinterpret_cast<const bf16x8*>(p.o + off);
-      bf16x8 y = *reinterpret_cast<const bf16x8*>(p.dout + off);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) acc = __builtin_fmaf((float)x[t], (float)y[t], acc);
+    for (int u = 0; u < UNROLL; ++u) {
+      const int r = r0 + u * RPP + rloc;
+      const int rr = r < rows ? r : rows - 1;   // clamped copies are computed and dropped
+      x[u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(o + (int64_t)rr * D + sub * 8));
+      y[u] = *reinterpret_cast<const bf16x8*>(dout + (int64_t)rr * D + sub * 8);
     }
 #pragma unroll
-    for (int s = LPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s, 64);
-    if (sub == 0 && i < p.S) {
-      p.delta[hh * p.S + i] = -acc;
-      p.lse2[hh * p.S + i] = -p.lse[hh * p.S + i] * kLog2e;
+    for (int u = 0; u < UNROLL; ++u) {
+      float acc = 0.f;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc = __builtin_fmaf((float)x[u][t], (float)y[u][t], acc);
+#pragma unroll
+      for (int s = LPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s, 64);
+      const int r = r0 + u * RPP + rloc;
+      if (sub == 0 && r < rows) s_delta[(r % p.Hq) * kTok + r / p.Hq] = -acc;
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < p.Hq * kTok; idx += kThreads) {
+    const int h = idx / kTok, t = idx % kTok;
+    if (t < ntok) {
+      const int64_t at = (b * p.Hq + h) * p.S + t0 + t;
+      p.delta[at] = s_delta[idx];
+      p.lse2[at] = -p.lse[at] * kLog2e;
     }
   }
 }
@@ -879,10 +897,14 @@ template <int D>
 static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
   hipError_t e;
   if (phases & 1) {  // delta
-    constexpr int rows_per_block = (kThreads / (D / 8)) * 8;
-    int64_t grid = ceil_div(p.S, rows_per_block) * p.B * p.Hq;
+    AttnParams a = p;
+    a.tiles = kDeltaTokens;
+    while (a.tiles > 1 && (size_t)p.Hq * a.tiles * sizeof(float) > 48 * 1024) a.tiles /= 2;
+    const size_t smem = (size_t)p.Hq * a.tiles * sizeof(float);
+    if (smem > 48 * 1024) return kErrShape;   // more than 12288 query heads per GPU
+    int64_t grid = ceil_div(p.S, a.tiles) * p.B;
     if (grid >= ((int64_t)1 << 31)) return kErrShape;
-    attn_bwd_delta_kernel<D><<<dim3((unsigned)grid), dim3(kThreads), 0, st>>>(p);
+    attn_bwd_delta_kernel<D><<<dim3((unsigned)grid), dim3(kThreads), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
   }
   // With room for dS in the workspace (p.ds), dK/dV runs first and stores it, and dQ is one product.

@@ -1,7 +1,10 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
-The oracle cannot run whole heads of a 128K sequence in test time, so it computes sampled
-outputs one by one: blocks of query rows (o, lse, dq need only those rows) and blocks of
+Where the oracle finishes a whole head in test time (a 32K head takes seconds, a head of the packed
+256K configuration under a minute) every element of that head is compared: the first and the last
+head of the headline configuration on both backward paths, and one head of the packed configuration.
+It cannot run whole heads of a 128K sequence, so there (and on top of the whole heads) it computes
+sampled outputs one by one: blocks of query rows (o, lse, dq need only those rows) and blocks of
 key columns (dk, dv need the forward statistics of every later row of the document, which
 the oracle computes first).  Blocks are placed at the start, across tile boundaries, at
 document boundaries and at the end.  On top of that, identities that hold at any size are
@@ -11,7 +14,7 @@ import numpy as np
 import pytest
 import torch
 
-from parity_util import TOL_GRAD_ABS, TOL_GRAD_REL, TOL_LSE, TOL_O, grad_errors
+from parity_util import TOL_GRAD_ABS, TOL_GRAD_REL, TOL_LSE, TOL_O, compare_all, grad_errors
 
 pytestmark = pytest.mark.gpu
 
@@ -76,6 +79,20 @@ def check_cols(oracle, cfg, cu, cpu_in, gpu_out, g, cols):
             assert ea <= TOL_GRAD_ABS and er <= TOL_GRAD_REL
 
 
+def check_head(oracle, cfg, cu, cpu_in, gpu_out, g):
+    """Every element of one kv head's group: o, lse, dq of its query heads and dk, dv, against the oracle's three
+    passes over the full sequence (seconds per 32K head on the host cores)."""
+    q, k, v, do = cpu_in
+    rep = cfg.Hq // cfg.Hkv
+    hs = slice(g * rep, (g + 1) * rep)
+    print(f"  whole kv head {g} (q heads {g * rep}..{(g + 1) * rep - 1}): oracle over all {cfg.S} tokens", flush=True)
+    ref = oracle.attn_fwd_bwd(w64(q[:, :, hs]), w64(k[:, :, g:g + 1]), w64(v[:, :, g:g + 1]), w64(do[:, :, hs]),
+                              cfg.scale, cfg.causal, cu)
+    o, lse, dq, dk, dv = gpu_out
+    got = (o[:, :, hs], lse[:, hs], dq[:, :, hs], dk[:, :, g:g + 1], dv[:, :, g:g + 1])
+    compare_all(got, ref, f"  whole kv head {g}")
+
+
 def check_identities(cfg, cu, gpu_in, gpu_out):
     """Properties of the exact gradients that need no oracle (all sums in fp64 on the GPU):
     <q,dq> over a group = <k,dk>; <v,dv> = <o,dO> over the group; sum_j dk_j = 0 per document."""
@@ -112,6 +129,8 @@ def test_config1_s32k_h32(oracle, stored_ds):
     check_rows(oracle, cfg, cu, cpu_in, gpu_out, 0, [(0, 40), (8180, 8200), (S - 33, S)])
     check_rows(oracle, cfg, cu, cpu_in, gpu_out, 31, [(16370, 16400)])
     check_cols(oracle, cfg, cu, cpu_in, gpu_out, 5, [(S - 200, S - 150), (20470, 20490)])
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 0)     # all rows and all columns of the first and the last head
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 31)
     check_identities(cfg, cu, gpu_in, gpu_out)
 
 
@@ -134,6 +153,7 @@ def test_config2_s128k_h8(oracle):
     S = cfg.S
     check_rows(oracle, cfg, cu, cpu_in, gpu_out, 3, [(0, 20), (65530, 65545), (S - 20, S)])
     check_cols(oracle, cfg, cu, cpu_in, gpu_out, 7, [(S - 130, S - 100), (110580, 110600)])
+    check_cols(oracle, cfg, cu, cpu_in, gpu_out, 2, [(0, 32)])   # the first key block: the longest query loop
     check_identities(cfg, cu, gpu_in, gpu_out)
 
 
@@ -163,4 +183,5 @@ def test_config4_packed_256k(oracle):
     short = int(np.argmin(np.where(lens > 0, lens, 1 << 30)))
     sa, se = int(cu[short]), int(cu[short + 1])
     check_cols(oracle, cfg, cu, cpu_in, gpu_out, 2, [(sa, min(se, sa + 64)), (e - 300, e - 270), (a + 130, a + 140) if e - a < 20000 else (e - 9000, e - 8990)])
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 3)     # every document of one head, element by element
     check_identities(cfg, cu, gpu_in, gpu_out)
