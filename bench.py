@@ -237,6 +237,7 @@ def main():
     ap.add_argument("--stored-ds", action="store_true",
                     help="time the optional backward path that keeps dS in a B*Hq*S*(S+128)-byte workspace as the step's backward "
                          "(default: the O(S)-workspace path; the other one is reported under bwd.other_path)")
+    ap.add_argument("--no-other-path", action="store_true", help="do not time the other backward path beside the step's own")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -304,7 +305,7 @@ def main():
 
     # the other backward path, for comparison; not part of `value`
     other = None
-    if has_ds_path and (stored_ds or ds_bytes <= 64e9):
+    if has_ds_path and not args.no_other_path and (stored_ds or ds_bytes <= 64e9):
         ws_o = binding.alloc_bwd_workspace(q, k, cu, fast=not stored_ds, causal=cfg.causal)
         bwd_o = lambda ph=binding.BWD_ALL: binding.ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu, cfg.scale,
                                                                       cfg.causal, ws_o, ph, stored_ds=not stored_ds)

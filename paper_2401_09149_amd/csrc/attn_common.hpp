@@ -415,12 +415,16 @@ struct TileCoord {
 template <int TS>
 __device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads, bool heavy_last, int* scratch, int w, int tid) {
   TileCoord c;
-  int nH = (int)p.B * heads;
+  // (the divisors below are the same for every item of a launch; they are made opaque so that a persistent kernel
+  // does not compute their reciprocals ahead of its item loop and keep them in registers through it)
+  auto opaque = [](int x) { asm volatile("" : "+s"(x)); return x; };
+  heads = opaque(heads);
+  const int nH = opaque((int)p.B * heads);
   int hh, t;
   if (nH % 8 == 0) {
     const int xcd = w & 7, slot = w >> 3;
-    const int hpx = nH / 8;                        // heads per list
-    const int heavy = p.tiles - p.tiles * 3 / 8;   // tiles per head in the head-by-head part
+    const int hpx = opaque(nH / 8);                        // heads per list
+    const int heavy = opaque(p.tiles - p.tiles * 3 / 8);   // tiles per head in the head-by-head part
     if (slot < heavy * hpx) { hh = xcd + 8 * (slot / heavy); t = slot % heavy; }
     else { const int r = slot - heavy * hpx; hh = xcd + 8 * (r % hpx); t = heavy + r / hpx; }
   } else {
