@@ -132,6 +132,27 @@ int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* 
                        void* workspace, size_t workspace_bytes, int32_t phases, void* stream);
 
 /*
+ * The same forward and backward passes with q, k, v read where the first sequence-parallel all-to-all left them,
+ * and dq, dk, dv written where the returning all-to-all picks them up: the re-layouts ie_sp_unpack_qkv and
+ * ie_sp_pack_dqkv (ie_sp.h) disappear from the layer (Sec. 2.4 "SP-2": after the exchange every GPU holds the
+ * complete sequence of Q, K, V for its heads; Sec. 3.2.2: the same exchanges run in the backward pass).
+ * `xqkv` is the received exchange buffer of ie_sp.h, [P][B][ q:[Sl][Hq/P][D] | k:[Sl][Hkv/P][D] | v:[Sl][Hkv/P][D] ]
+ * (chunk p = tokens [p*Sl, (p+1)*Sl) of this GPU's heads), `dxqkv` a buffer of the same layout that receives
+ * dq | dk | dv.  o, dout [B][P*Sl][Hq/P][D] and lse [B][Hq/P][P*Sl] are as in ie_attn_fwd / ie_attn_bwd (with B == 1
+ * that IS the layout the second exchange sends and receives).  Hq, Hkv are the head counts of the whole layer, both
+ * divisible by P; Sl must be a power of two and at least 256 (IE_ERR_UNSUPPORTED otherwise: use the re-layouts);
+ * dense input only.  The workspace is that of ie_attn_bwd for (B, P*Sl, Hq/P, Hkv/P, D).  Results are bit-identical
+ * to unpacking, calling ie_attn_fwd / ie_attn_bwd and packing.
+ */
+int ie_attn_fwd_sp(const void* xqkv, void* o, float* lse,
+                   int64_t B, int64_t Sl, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                   float scale, int32_t causal, void* stream);
+int ie_attn_bwd_sp(const void* xqkv, const void* o, const void* dout, const float* lse, void* dxqkv,
+                   int64_t B, int64_t Sl, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                   float scale, int32_t causal,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * ie_attn_bwd for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  The same computation and the same kernels as ie_attn_bwd(...) with the minimal
  * workspace, but the workspace is a device array inside the library (IE_ATTN_BWD_STATIC_MAX_ROWS * 8 + 256 bytes,

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("IE_ATTN_LIB") or os.path.join(_HERE, "libie_attn.so")  # override: for trying out a build
 
 EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd_fast_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases",
-           "ie_attn_bwd_static", "ie_attn_strerror",
+           "ie_attn_bwd_static", "ie_attn_fwd_sp", "ie_attn_bwd_sp", "ie_attn_strerror",
            "ie_attn_last_hip_error",
            "ie_sp_pack_qkv", "ie_sp_unpack_qkv", "ie_sp_pack_o", "ie_sp_unpack_o",
            "ie_sp_pack_do", "ie_sp_unpack_do", "ie_sp_pack_dqkv", "ie_sp_unpack_dqkv",
@@ -50,6 +50,10 @@ def load():
     lib.ie_attn_bwd_phases.restype = ctypes.c_int
     lib.ie_attn_bwd_static.argtypes = [vp] * 9 + [vp, i32, i64, i64, i32, i32, i32, f32, i32, vp]
     lib.ie_attn_bwd_static.restype = ctypes.c_int
+    lib.ie_attn_fwd_sp.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, f32, i32, vp]
+    lib.ie_attn_fwd_sp.restype = ctypes.c_int
+    lib.ie_attn_bwd_sp.argtypes = [vp] * 5 + [i64, i64, i32, i32, i32, i32, f32, i32, vp, ctypes.c_size_t, vp]
+    lib.ie_attn_bwd_sp.restype = ctypes.c_int
     lib.ie_attn_strerror.argtypes = [ctypes.c_int]
     lib.ie_attn_strerror.restype = ctypes.c_char_p
     lib.ie_attn_last_hip_error.argtypes = []
@@ -175,6 +179,35 @@ def ie_attn_bwd_static(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, scale, cau
                                    _ptr(dout, bf, "dout"), _ptr(lse, torch.float32, "lse"), _ptr(dq, bf, "dq"),
                                    _ptr(dk, bf, "dk"), _ptr(dv, bf, "dv"), cu, nd, B, S, Hq, Hkv, D, float(scale),
                                    int(bool(causal)), _stream(stream))
+    if rc != 0:
+        _raise(rc)
+
+
+def _sp_sizes(B, Sl, Hq, Hkv, D, P):
+    _check_heads(Hq, Hkv, P)
+    return B * Sl * (Hq + 2 * Hkv) * D, (B, P * Sl, Hq // P, D), (B, Hq // P, P * Sl)
+
+
+def ie_attn_fwd_sp(xqkv, o, lse, B, Sl, Hq, Hkv, D, P, scale, causal, stream=None):
+    """ie_attn_fwd on the received exchange buffer `xqkv` (layout of ie_sp.h); o [B,P*Sl,Hq/P,D], lse [B,Hq/P,P*Sl]."""
+    n, o_shape, lse_shape = _sp_sizes(B, Sl, Hq, Hkv, D, P)
+    if tuple(o.shape) != o_shape or tuple(lse.shape) != lse_shape:
+        raise ValueError(f"o / lse must have shapes {o_shape} / {lse_shape}")
+    rc = load().ie_attn_fwd_sp(_buf(xqkv, n, "xqkv"), _ptr(o, torch.bfloat16, "o"), _ptr(lse, torch.float32, "lse"),
+                               B, Sl, Hq, Hkv, D, P, float(scale), int(bool(causal)), _stream(stream))
+    if rc != 0:
+        _raise(rc)
+
+
+def ie_attn_bwd_sp(xqkv, o, dout, lse, dxqkv, B, Sl, Hq, Hkv, D, P, scale, causal, workspace, stream=None):
+    """ie_attn_bwd on the received exchange buffer; dq | dk | dv go to `dxqkv` in the layout the returning exchange sends."""
+    n, o_shape, lse_shape = _sp_sizes(B, Sl, Hq, Hkv, D, P)
+    if tuple(o.shape) != o_shape or tuple(dout.shape) != o_shape or tuple(lse.shape) != lse_shape:
+        raise ValueError(f"o, dout / lse must have shapes {o_shape} / {lse_shape}")
+    bf = torch.bfloat16
+    rc = load().ie_attn_bwd_sp(_buf(xqkv, n, "xqkv"), _ptr(o, bf, "o"), _ptr(dout, bf, "dout"), _ptr(lse, torch.float32, "lse"),
+                               _buf(dxqkv, n, "dxqkv"), B, Sl, Hq, Hkv, D, P, float(scale), int(bool(causal)),
+                               _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     if rc != 0:
         _raise(rc)
 

@@ -120,16 +120,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
 
   const int64_t q_stride = (int64_t)p.Hq * D;
   const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
-  const int64_t qhead = ((int64_t)tc.b * p.S * p.Hq + tc.h) * D;
-  const char* kbase = reinterpret_cast<const char*>(p.k + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D);
-  const char* vbase = reinterpret_cast<const char*>(p.v + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D);
-  const int64_t tile_pitch = BN * kv_pitch;
+  const int64_t qhead = ((int64_t)tc.b * p.S * p.Hq + tc.h) * D;   // for dout (always contiguous)
+  // (wave-uniform values that came through LDS are moved to scalar registers explicitly)
+  const char* kbase = uniform(reinterpret_cast<const char*>(p.k + g * D) + tc.b * p.kv_bstride);   // key tile kt starts at token k_begin + kt * BN
+  const char* vbase = uniform(reinterpret_cast<const char*>(p.v + g * D) + tc.b * p.kv_bstride);
+  const int64_t k_begin_u = uniform(k_begin);
+  auto key_tile_off = [&](const int kt) __attribute__((always_inline)) { return tok_off(p, k_begin_u + (int64_t)kt * BN, kv_pitch); };
 
   const uint32_t lds0 = lds_address(smem);
   AsyncTile<D> ld;
   ld.init(tid, kv_pitch);
-  ld.load(lds0, kbase, nk);
-  ld.load(lds0 + TILE_BYTES, vbase, nk);
+  ld.load(lds0, kbase + key_tile_off(0), nk);
+  ld.load(lds0 + TILE_BYTES, vbase + key_tile_off(0), nk);
 
   int64_t row = q0 + wv * 32 + n;
   const bool row_ok = row < q_end;
@@ -139,7 +141,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   bf16x8 qf[NKS], dof[NKS];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    qf[ks] = *reinterpret_cast<const bf16x8*>(p.q + qhead + row * q_stride + ks * 16 + h * 8);
+    qf[ks] = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const char*>(p.q + tc.h * D) + tc.b * p.q_bstride +
+                                              tok_off(p, row, q_stride * 2) + (ks * 16 + h * 8) * 2);
     dof[ks] = *reinterpret_cast<const bf16x8*>(p.dout + qhead + row * q_stride + ks * 16 + h * 8);
   }
   const int64_t stat = ((int64_t)tc.b * p.Hq + tc.h) * p.S + row;
@@ -175,11 +178,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
     const int kb = kt * BN;
     const uint32_t next_lds = lds0 + (STAGE_BYTES - stage);
     if (full_next) {
-      ld.load_full(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch);
-      ld.load_full(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch);
+      ld.load_full(next_lds, kbase + key_tile_off(kt + 1));
+      ld.load_full(next_lds + TILE_BYTES, vbase + key_tile_off(kt + 1));
     } else if (kt + 1 < nkt) {
-      ld.load(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch, nk - kb - BN);
-      ld.load(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch, nk - kb - BN);
+      ld.load(next_lds, kbase + key_tile_off(kt + 1), nk - kb - BN);
+      ld.load(next_lds + TILE_BYTES, vbase + key_tile_off(kt + 1), nk - kb - BN);
     }
     const bool need_mask = (p.causal && kb + BN - 1 > wave_row_min) || (kb + BN > nk);
     const int lim = (p.causal ? row_rel : nk - 1) - kb - 4 * h;
@@ -247,7 +250,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   }
   for (; kt < nkt; ++kt) tile_step(kt, (kt & 1) * STAGE_BYTES, std::false_type{});
 
-  __bf16* drow = p.dq + qhead + row * q_stride;
+  // (the row is formed again from its 32-bit position: a 64-bit row index kept alive through the main loop is two
+  // registers this kernel does not have)
+  __bf16* drow = reinterpret_cast<__bf16*>(reinterpret_cast<char*>(p.dq + tc.h * D) + tc.b * p.q_bstride +
+                                           tok_off(p, k_begin_u + row_rel, q_stride * 2));
 #pragma unroll
   for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc[db], p.scale, h, row_ok);
   }  // next item
@@ -271,8 +277,11 @@ struct DkdvCfg {
   static constexpr int SMEM_BYTES = STAGES * STAGE_BYTES;
 };
 
-template <int D, bool STORE_DS>
+// CHUNKED: q, k, v, dk, dv are chunks of a sequence-parallel exchange buffer (tok_off in attn_common.hpp) instead of
+// contiguous tensors: a separate instantiation, so that the contiguous case keeps its simpler address arithmetic.
+template <int D, bool STORE_DS, bool CHUNKED = false>
 __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p) {
+  static_assert(!(STORE_DS && CHUNKED), "the stored-dS path takes contiguous tensors");
   using C = DkdvCfg<D>;
   constexpr int BK = C::BK, BQ = C::BQ, NB = C::NB;
   constexpr int NKS = D / 16, NDB = D / 32;
@@ -306,8 +315,13 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   const int total = nqt * group;               // loop steps: query heads of the group x query tiles
 
   const int64_t q_pitch = (int64_t)p.Hq * D * 2;  // bytes between consecutive tokens of one query head
-  const int64_t kv_stride = (int64_t)p.Hkv * D;
-  const int64_t kvhead = ((int64_t)tc.b * p.S * p.Hkv + g) * D;
+  const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;   // bytes between consecutive tokens of one kv head
+  // bytes: head g of the batch entry's first token
+  const int64_t kvhead = CHUNKED ? tc.b * p.kv_bstride + (int64_t)g * D * 2 : ((int64_t)tc.b * p.S * p.Hkv + g) * D * 2;
+  auto kv_row_off = [&](const int64_t t) __attribute__((always_inline)) {
+    if constexpr (CHUNKED) return tok_off(p, t, kv_pitch);
+    else return t * kv_pitch;
+  };
 
   const uint32_t lds0 = lds_address(smem);
   AsyncTile<D> ld;
@@ -333,7 +347,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     const int i0 = tile_idx * BQ;  // first row of the tile, relative to q_begin
     t.rows = nq - i0;
     const int64_t tok = (int64_t)tc.b * p.S + q_begin + i0;
-    t.qg = reinterpret_cast<const char*>(p.q + (tok * p.Hq + hq) * D);
+    if constexpr (CHUNKED) t.qg = reinterpret_cast<const char*>(p.q + hq * D) + tc.b * p.q_bstride + tok_off(p, q_begin + i0, q_pitch);
+    else t.qg = reinterpret_cast<const char*>(p.q + (tok * p.Hq + hq) * D);
     t.dog = reinterpret_cast<const char*>(p.dout + (tok * p.Hq + hq) * D);
     const int64_t idx = ((int64_t)tc.b * p.Hq + hq) * p.S + q_begin + i0;
     t.stat = reinterpret_cast<const char*>((wave_u < 2 ? p.lse2 : p.delta) + idx);
@@ -395,8 +410,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   bf16x8 kf[NKS], vf[NKS];                   // live in AGPRs
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    kf[ks] = global_load_to_agpr(p.k + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
-    vf[ks] = global_load_to_agpr(p.v + kvhead + key_ld * kv_stride + ks * 16 + h * 8);
+    kf[ks] = global_load_to_agpr(reinterpret_cast<const char*>(p.k) + kvhead + kv_row_off(key_ld) + (ks * 16 + h * 8) * 2);
+    vf[ks] = global_load_to_agpr(reinterpret_cast<const char*>(p.v) + kvhead + kv_row_off(key_ld) + (ks * 16 + h * 8) * 2);
   }
 
   // Per-lane LDS addresses for each stage; block, tile and k-step offsets are immediates.
@@ -734,8 +749,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   mfma_result_fence();  // the last assembly MFMAs have retired before the accumulators are read
 
   const int64_t key_st = key_ok ? key : tc.doc_end - 1;  // (address only formed for rows that exist)
-  __bf16* dkrow = p.dk + kvhead + key_st * kv_stride;
-  __bf16* dvrow = p.dv + kvhead + key_st * kv_stride;
+  __bf16* dkrow = reinterpret_cast<__bf16*>(reinterpret_cast<char*>(p.dk) + kvhead + kv_row_off(key_st));
+  __bf16* dvrow = reinterpret_cast<__bf16*>(reinterpret_cast<char*>(p.dv) + kvhead + kv_row_off(key_st));
 #pragma unroll
   for (int db = 0; db < NDB; ++db) {
     store_block32_bf16(dkrow + 32 * db, dkacc[db], p.scale, h, key_ok);
@@ -789,7 +804,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
   const int nkt = has_b && causal ? nkt_a + 128 / BN : nkt_a;
 
   const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
-  const char* kbase = reinterpret_cast<const char*>(p.k + ((int64_t)tc.b * p.S * p.Hkv + g) * D);
+  const char* kbase = reinterpret_cast<const char*>(p.k + g * D) + tc.b * p.kv_bstride;   // (this path takes contiguous tensors only)
   const int64_t bh = (int64_t)tc.b * p.Hq + tc.h;
   const char* sa = reinterpret_cast<const char*>(p.ds) + ds_matrix_offset(p.S / 128, bh, ita, causal);
   const char* sb = has_b ? sa + ds_matrix_bytes(p.S / 128, ita, causal) : sa;   // (without a second tile: valid memory, never used)
@@ -940,12 +955,12 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
     return 0;
   };
-  auto dkdv_phase = [&](auto store_c) -> int {
-    constexpr bool kStore = decltype(store_c)::value;
+  auto dkdv_phase = [&](auto store_c, auto chunked_c) -> int {
+    constexpr bool kStore = decltype(store_c)::value, kChunked = decltype(chunked_c)::value;
     constexpr int smem = DkdvCfg<D>::SMEM_BYTES;
     static KernelSetup setup;
     int per_cu = 1;
-    int rc = kernel_setup(setup, attn_bwd_dkdv_kernel<D, kStore>, smem, &per_cu);
+    int rc = kernel_setup(setup, attn_bwd_dkdv_kernel<D, kStore, kChunked>, smem, &per_cu);
     if (rc) return rc;
     int64_t tiles = tiles_per_head(p.S, 128, p.cu, p.num_docs);
     int64_t items = tiles * p.B * p.Hkv;
@@ -954,19 +969,20 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     a.tiles = (int32_t)tiles;
     const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDkdv, items, a.Hkv, per_cu, st);
     if (ql.err != hipSuccess) return hip_fail(ql.err);
-    attn_bwd_dkdv_kernel<D, kStore><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
+    attn_bwd_dkdv_kernel<D, kStore, kChunked><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
     return 0;
   };
+  const bool chunked = p.tok_shift < 63;
   int rc = 0;
   if (from_ds) {
     if constexpr (D == 128) {
-      if ((phases & 4) && (rc = dkdv_phase(std::true_type{}))) return rc;
+      if ((phases & 4) && (rc = dkdv_phase(std::true_type{}, std::false_type{}))) return rc;
     }
     if ((phases & 2) && (rc = dq_phase())) return rc;
   } else {
     if ((phases & 2) && (rc = dq_phase())) return rc;
-    if ((phases & 4) && (rc = dkdv_phase(std::false_type{}))) return rc;
+    if ((phases & 4) && (rc = chunked ? dkdv_phase(std::false_type{}, std::true_type{}) : dkdv_phase(std::false_type{}, std::false_type{}))) return rc;
   }
   return 0;
 }

@@ -48,6 +48,12 @@ struct AttnParams {
   int32_t tiles;            // tiles per head the grid was sized for (upper bound when packed)
   int32_t q_reserved, q_per_xcd, q_total;  // persistent launches (tile_queue.hpp): items per XCD list (0: one list), items
   __bf16* ds;               // optional workspace: dS written by the dK/dV kernel for the dQ kernel (see ds_matrix_offset), or NULL
+  // Where token t of batch entry b lives in q/dq (pitch Hq*D) and k/v/dk/dv (pitch Hkv*D), see tok_off():
+  // contiguous [B,S,heads,D] tensors, or the chunks of a sequence-parallel exchange buffer (one chunk per peer).
+  int32_t tok_shift;              // log2(tokens per chunk); 63 for contiguous tensors
+  int64_t tok_mask;               // tokens per chunk - 1; all ones for contiguous tensors
+  int64_t tok_cstride;            // bytes between consecutive chunks of one batch entry
+  int64_t q_bstride, kv_bstride;  // bytes between batch entries
   unsigned int* q_counters;       // persistent launches: this launch's eight work-queue counters
   unsigned int* ws_counters;      // backward: counter blocks in the caller's workspace (kQueueBytes each, one per kernel)
 };
@@ -66,6 +72,13 @@ __host__ __device__ inline int64_t ds_matrix_offset(int64_t nt, int64_t bh, int6
 }
 // Bytes between the blocks of query tiles it and it + 1 of one head.
 __host__ __device__ inline int64_t ds_matrix_bytes(int64_t nt, int64_t it, bool causal) { return (causal ? it + 1 : nt) * 32768; }
+
+// Byte offset of token t (0 <= t < S) inside its batch entry, for q, k, v and their gradients; `pitch` = bytes per
+// token (heads * D * 2).  Contiguous tensors: t * pitch.  Exchange-buffer chunks of 2^tok_shift tokens: the chunk's
+// offset plus the row's.
+__device__ __forceinline__ int64_t tok_off(const AttnParams& p, int64_t t, int64_t pitch) {
+  return (t >> p.tok_shift) * p.tok_cstride + (t & p.tok_mask) * pitch;
+}
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -285,6 +298,8 @@ __device__ __forceinline__ const char* uniform(const char* p) {
   const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
   return (const char*)(lo | (hi << 32));
 }
+
+__device__ __forceinline__ int64_t uniform(int64_t x) { return (int64_t)(uintptr_t)uniform((const char*)(uintptr_t)x); }
 
 __device__ __forceinline__ void async_copy16(uint32_t voffset, const char* sbase, uint32_t lds_addr) {
   sbase = uniform(sbase);

@@ -42,16 +42,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
 
   const int64_t q_stride = (int64_t)p.Hq * D;
   const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;  // bytes between consecutive tokens of one kv head
-  const __bf16* qbase = p.q + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D;
-  const char* kbase = reinterpret_cast<const char*>(p.k + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D);
-  const char* vbase = reinterpret_cast<const char*>(p.v + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D);
-  const int64_t tile_pitch = BN * kv_pitch;
+  const char* qbase = reinterpret_cast<const char*>(p.q + tc.h * D) + tc.b * p.q_bstride;
+  const char* kbase = reinterpret_cast<const char*>(p.k + g * D) + tc.b * p.kv_bstride;   // key tile kt starts at token k_begin + kt * BN
+  const char* vbase = reinterpret_cast<const char*>(p.v + g * D) + tc.b * p.kv_bstride;
+  auto key_tile_off = [&](const int kt) __attribute__((always_inline)) { return tok_off(p, k_begin + (int64_t)kt * BN, kv_pitch); };
 
   const uint32_t lds0 = lds_address(smem);
   AsyncTile<D> ld;
   ld.init(tid, kv_pitch);
-  ld.load(lds0, kbase, nk);
-  ld.load(lds0 + TILE_BYTES, vbase, nk);
+  ld.load(lds0, kbase + key_tile_off(0), nk);
+  ld.load(lds0 + TILE_BYTES, vbase + key_tile_off(0), nk);
 
   // This lane's query row (clamped into the tile so that out-of-range lanes repeat the last row).
   int64_t row = q0 + wv * 32 + n;
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
   bf16x8 qf[NKS];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks)
-    qf[ks] = *reinterpret_cast<const bf16x8*>(qbase + row * q_stride + ks * 16 + h * 8);
+    qf[ks] = *reinterpret_cast<const bf16x8*>(qbase + tok_off(p, row, q_stride * 2) + (ks * 16 + h * 8) * 2);
 
   // Per-lane LDS addresses inside stage 0; stage, tile and row-block offsets are immediates.
   const char* k_ptr[NKS];  // K tile, A operand: row = key n (+32 for the second block), chunk = 2ks + h
@@ -101,11 +101,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(AttnParams p) {
     const int kb = kt * BN;  // first key of the tile, relative to k_begin
     const uint32_t next_lds = lds0 + (STAGE_BYTES - stage);
     if (full_next) {
-      ld.load_full(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch);
-      ld.load_full(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch);
+      ld.load_full(next_lds, kbase + key_tile_off(kt + 1));
+      ld.load_full(next_lds + TILE_BYTES, vbase + key_tile_off(kt + 1));
     } else if (kt + 1 < nkt) {
-      ld.load(next_lds, kbase + (int64_t)(kt + 1) * tile_pitch, nk - kb - BN);
-      ld.load(next_lds + TILE_BYTES, vbase + (int64_t)(kt + 1) * tile_pitch, nk - kb - BN);
+      ld.load(next_lds, kbase + key_tile_off(kt + 1), nk - kb - BN);
+      ld.load(next_lds + TILE_BYTES, vbase + key_tile_off(kt + 1), nk - kb - BN);
     }
     // Mask: only tiles that reach past the wave's first row (causal) or past the last key.
     const bool need_mask = (p.causal && kb + BN - 1 > wave_row_min) || (kb + BN > nk);

@@ -52,6 +52,9 @@ struct ColState {
   float l;      // this lane's share of the row sum
 };
 
+// CHUNKED: q, k, v are the chunks of a sequence-parallel exchange buffer (tok_off in attn_common.hpp) instead of
+// contiguous tensors; a separate instantiation, because this kernel has no register to spare for the general form.
+template <bool CHUNKED>
 __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p) {
   using C = FwdWideCfg;
   constexpr int D = C::D, BM = C::BM, BN = C::BN, NB = C::NB;
@@ -87,10 +90,23 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
 
   const int64_t q_stride = (int64_t)p.Hq * D;
   const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
-  const __bf16* qbase = p.q + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D;
-  const char* kbase = uniform(reinterpret_cast<const char*>(p.k + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D));
-  const char* vbase = uniform(reinterpret_cast<const char*>(p.v + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D));
+  // Head tc.h (g) of the batch entry's first token (CHUNKED) or of token k_begin (contiguous tensors); key tile T
+  // starts at token k_begin + T * BN.
+  const char* qbase = CHUNKED ? reinterpret_cast<const char*>(p.q + tc.h * D) + tc.b * p.q_bstride
+                              : reinterpret_cast<const char*>(p.q + ((int64_t)tc.b * p.S * p.Hq + tc.h) * D);
+  const char* kbase = uniform(CHUNKED ? reinterpret_cast<const char*>(p.k + g * D) + tc.b * p.kv_bstride
+                                      : reinterpret_cast<const char*>(p.k + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D));
+  const char* vbase = uniform(CHUNKED ? reinterpret_cast<const char*>(p.v + g * D) + tc.b * p.kv_bstride
+                                      : reinterpret_cast<const char*>(p.v + (((int64_t)tc.b * p.S + k_begin) * p.Hkv + g) * D));
   const int64_t tile_pitch = BN * kv_pitch;
+  auto key_tile_off = [&](const int T) __attribute__((always_inline)) {
+    if constexpr (CHUNKED) return tok_off(p, k_begin + (int64_t)T * BN, kv_pitch);
+    else return T * tile_pitch;
+  };
+  auto q_row_off = [&](const int64_t row) __attribute__((always_inline)) {
+    if constexpr (CHUNKED) return tok_off(p, row, q_stride * 2);
+    else return row * q_stride * 2;
+  };
 
   const uint32_t lds0 = lds_address(smem);
   AsyncTile<D> ld;
@@ -107,8 +123,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
     for (int part = 0; part < BN / 64; ++part) {
       const int first = rows > 64 * part ? 64 * part : rows - 1;  // a part past the end repeats the last row
       const int valid = rows > 64 * part ? rows - 64 * part : 1;
-      ld.load(base + part * C::PART_BYTES, kbase + T * tile_pitch + (int64_t)first * kv_pitch, valid);
-      ld.load(base + V_BASE + part * C::PART_BYTES, vbase + T * tile_pitch + (int64_t)first * kv_pitch, valid);
+      ld.load(base + part * C::PART_BYTES, kbase + key_tile_off(T) + (int64_t)first * kv_pitch, valid);
+      ld.load(base + V_BASE + part * C::PART_BYTES, vbase + key_tile_off(T) + (int64_t)first * kv_pitch, valid);
     }
   };
   // Piece k of a complete tile: instruction i of 64-row part `part` of tensor `tensor`.  The row
@@ -122,8 +138,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
     CopySrc cs;
 #pragma unroll
     for (int part = 0; part < BN / 64; ++part) {
-      cs.k[part] = kbase + T * tile_pitch + (int64_t)(64 * part) * kv_pitch;
-      cs.v[part] = vbase + T * tile_pitch + (int64_t)(64 * part) * kv_pitch;
+      cs.k[part] = kbase + key_tile_off(T) + (int64_t)(64 * part) * kv_pitch;
+      cs.v[part] = vbase + key_tile_off(T) + (int64_t)(64 * part) * kv_pitch;
     }
     cs.lds = lds0 + (T & 1) * TILE_BYTES + wave_u * 1024;
     return cs;
@@ -145,8 +161,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   bf16x8 qa[NKS], qb[NKS];  // live in AGPRs: B operand of S^T = K Q^T, column n = query
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    qa[ks] = global_load_to_agpr(qbase + row_a * q_stride + ks * 16 + h * 8);
-    qb[ks] = global_load_to_agpr(qbase + row_b * q_stride + ks * 16 + h * 8);
+    qa[ks] = global_load_to_agpr(qbase + q_row_off(row_a) + (ks * 16 + h * 8) * 2);
+    qb[ks] = global_load_to_agpr(qbase + q_row_off(row_b) + (ks * 16 + h * 8) * 2);
   }
 
   // Per-lane LDS addresses in stage 0; stage, block and half-block offsets are immediates.
@@ -600,9 +616,11 @@ void slot_release(int dev, int slot, hipStream_t st, bool capturing, bool launch
 
 int launch_fwd_wide(AttnParams p, hipStream_t st) {
   constexpr int smem = FwdWideCfg::SMEM_BYTES;
-  static KernelSetup setup;
+  const bool chunked = p.tok_shift < 63;
+  static KernelSetup setup[2];
   int per_cu = 1;
-  int rc = kernel_setup(setup, attn_fwd_wide_kernel, smem, &per_cu);
+  int rc = chunked ? kernel_setup(setup[1], attn_fwd_wide_kernel<true>, smem, &per_cu)
+                   : kernel_setup(setup[0], attn_fwd_wide_kernel<false>, smem, &per_cu);
   if (rc) return rc;
   int64_t tiles = tiles_per_head(p.S, FwdWideCfg::BM, p.cu, p.num_docs);
   int64_t items = tiles * p.B * p.Hq;
@@ -614,7 +632,8 @@ int launch_fwd_wide(AttnParams p, hipStream_t st) {
   if ((rc = slot_acquire(st, &dev, &slot, &counters, &capturing)) != 0) return rc;
   const QueueLaunch ql = tile_queue_prepare(p, counters, items, p.Hq, 1, st);
   if (ql.err != hipSuccess) { slot_release(dev, slot, st, capturing, false); return hip_fail(ql.err); }
-  attn_fwd_wide_kernel<<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
+  if (chunked) attn_fwd_wide_kernel<true><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
+  else attn_fwd_wide_kernel<false><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
   hipError_t e = hipGetLastError();
   slot_release(dev, slot, st, capturing, true);   // (the reset kernel is enqueued either way)
   return e == hipSuccess ? 0 : hip_fail(e);

@@ -4,6 +4,7 @@
 #include "../../include/ie_attn.h"
 
 #include <cmath>
+#include <cstdint>
 #include <cstring>
 #include <mutex>
 
@@ -22,7 +23,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 size_t stat_bytes(int64_t B, int64_t S, int32_t Hq) { return align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256); }
 constexpr size_t kCounterBytes = 256;
 
-ie::AttnParams base_params(const int32_t* cu, int32_t num_docs, int64_t B, int64_t S, int32_t Hq, int32_t Hkv,
+ie::AttnParams base_params(const int32_t* cu, int32_t num_docs, int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
                            float scale, int32_t causal) {
   ie::AttnParams p;
   std::memset(&p, 0, sizeof(p));
@@ -32,6 +33,12 @@ ie::AttnParams base_params(const int32_t* cu, int32_t num_docs, int64_t B, int64
   p.scale = scale;
   p.scale_log2 = scale * ie::kLog2e;
   p.causal = causal;
+  // contiguous [B,S,heads,D] tensors: one "chunk" per batch entry
+  p.tok_shift = 63;
+  p.tok_mask = INT64_MAX;
+  p.tok_cstride = 0;
+  p.q_bstride = S * (int64_t)Hq * D * 2;
+  p.kv_bstride = S * (int64_t)Hkv * D * 2;
   return p;
 }
 
@@ -80,7 +87,7 @@ int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
   if (!q || !k || !v || !o || !lse) return IE_ERR_NULL;
   int rc = check_shape(cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal);
   if (rc) return rc;
-  ie::AttnParams p = base_params(cu_seqlens, num_docs, B, S, Hq, Hkv, scale, causal);
+  ie::AttnParams p = base_params(cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal);
   p.q = static_cast<const __bf16*>(q);
   p.k = static_cast<const __bf16*>(k);
   p.v = static_cast<const __bf16*>(v);
@@ -135,7 +142,7 @@ int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* 
     if (required == need) return IE_ERR_UNSUPPORTED;   // this shape has no such path
   }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < required) return IE_ERR_WORKSPACE;
-  ie::AttnParams p = base_params(cu_seqlens, num_docs, B, S, Hq, Hkv, scale, causal);
+  ie::AttnParams p = base_params(cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal);
   p.q = static_cast<const __bf16*>(q);
   p.k = static_cast<const __bf16*>(k);
   p.v = static_cast<const __bf16*>(v);
@@ -181,6 +188,80 @@ int ie_attn_bwd_static(const void* q, const void* k, const void* v, const void* 
   // planes for all B*Hq*S rows, the reset kernels clear the counters), so nothing has to be cleared here.
   return ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal,
                             ptr, kStaticBytes, IE_BWD_ALL, stream);
+}
+
+// ---- operands taken from / gradients written to the sequence-parallel exchange buffer --------------------
+// Token t of batch entry b sits in chunk t / Sl (the peer it came from) at row t % Sl; the three planes of a chunk
+// follow each other.  Tiles of the kernels (at most 256 tokens, aligned) must not straddle chunks, and the kernels
+// split t with a shift and a mask: Sl is a power of two, at least 256.
+static int sp_shape(int64_t B, int64_t Sl, int32_t Hq, int32_t Hkv, int32_t D, int32_t P, float scale, int32_t causal) {
+  if (P < 1 || Sl < 1 || Hq < 1 || Hkv < 1 || Hq % P != 0 || Hkv % P != 0) return IE_ERR_SHAPE;
+  if (Sl > (((int64_t)1 << 31) - 1) / P) return IE_ERR_SHAPE;
+  int rc = check_shape(nullptr, 0, B, Sl * P, Hq / P, Hkv / P, D, scale, causal);
+  if (rc) return rc;
+  if (Sl < 256 || (Sl & (Sl - 1)) != 0) return IE_ERR_UNSUPPORTED;
+  return IE_OK;
+}
+
+static void sp_token_map(ie::AttnParams& p, int64_t B, int64_t Sl, int32_t Hql, int32_t Hkvl, int32_t D) {
+  const int64_t chunk_bytes = Sl * (int64_t)(Hql + 2 * Hkvl) * D * 2;
+  int shift = 0;
+  while (((int64_t)1 << shift) < Sl) ++shift;
+  p.tok_shift = shift;
+  p.tok_mask = Sl - 1;
+  p.tok_cstride = B * chunk_bytes;
+  p.q_bstride = chunk_bytes;
+  p.kv_bstride = chunk_bytes;
+}
+
+int ie_attn_fwd_sp(const void* xqkv, void* o, float* lse, int64_t B, int64_t Sl, int32_t Hq, int32_t Hkv, int32_t D,
+                   int32_t P, float scale, int32_t causal, void* stream) {
+  if (!xqkv || !o || !lse) return IE_ERR_NULL;
+  int rc = sp_shape(B, Sl, Hq, Hkv, D, P, scale, causal);
+  if (rc) return rc;
+  if ((reinterpret_cast<uintptr_t>(xqkv) & 15) != 0) return IE_ERR_ALIGN;
+  const int32_t Hql = Hq / P, Hkvl = Hkv / P;
+  ie::AttnParams p = base_params(nullptr, 0, B, Sl * P, Hql, Hkvl, D, scale, causal);
+  sp_token_map(p, B, Sl, Hql, Hkvl, D);
+  const __bf16* x = static_cast<const __bf16*>(xqkv);
+  p.q = x;
+  p.k = x + Sl * (int64_t)Hql * D;
+  p.v = x + Sl * (int64_t)(Hql + Hkvl) * D;
+  p.o_out = static_cast<__bf16*>(o);
+  p.lse_out = lse;
+  return ie::launch_fwd(p, D, static_cast<hipStream_t>(stream));
+}
+
+int ie_attn_bwd_sp(const void* xqkv, const void* o, const void* dout, const float* lse, void* dxqkv, int64_t B,
+                   int64_t Sl, int32_t Hq, int32_t Hkv, int32_t D, int32_t P, float scale, int32_t causal,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (!xqkv || !o || !dout || !lse || !dxqkv) return IE_ERR_NULL;
+  int rc = sp_shape(B, Sl, Hq, Hkv, D, P, scale, causal);
+  if (rc) return rc;
+  if (((reinterpret_cast<uintptr_t>(xqkv) | reinterpret_cast<uintptr_t>(dxqkv)) & 15) != 0) return IE_ERR_ALIGN;
+  const int32_t Hql = Hq / P, Hkvl = Hkv / P;
+  const int64_t S = Sl * P;
+  const size_t need = ie_attn_bwd_workspace_bytes(B, S, Hql, Hkvl, D, 0);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < need) return IE_ERR_WORKSPACE;
+  ie::AttnParams p = base_params(nullptr, 0, B, S, Hql, Hkvl, D, scale, causal);
+  sp_token_map(p, B, Sl, Hql, Hkvl, D);
+  const __bf16* x = static_cast<const __bf16*>(xqkv);
+  __bf16* dx = static_cast<__bf16*>(dxqkv);
+  p.q = x;
+  p.k = x + Sl * (int64_t)Hql * D;
+  p.v = x + Sl * (int64_t)(Hql + Hkvl) * D;
+  p.dq = dx;
+  p.dk = dx + Sl * (int64_t)Hql * D;
+  p.dv = dx + Sl * (int64_t)(Hql + Hkvl) * D;
+  p.o = static_cast<const __bf16*>(o);
+  p.dout = static_cast<const __bf16*>(dout);
+  p.lse = lse;
+  char* ws = static_cast<char*>(workspace);
+  p.delta = reinterpret_cast<float*>(ws);
+  p.lse2 = reinterpret_cast<float*>(ws + stat_bytes(B, S, Hql));
+  p.ws_counters = reinterpret_cast<unsigned int*>(ws + 2 * stat_bytes(B, S, Hql));
+  p.ds = nullptr;
+  return ie::launch_bwd(p, D, IE_BWD_ALL, static_cast<hipStream_t>(stream));
 }
 
 const char* ie_attn_strerror(int code) {

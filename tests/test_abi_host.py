@@ -109,6 +109,24 @@ def test_bad_arguments_fail_before_any_launch(lib):
     assert static(S=(1 << 21) // 4 + 1) == -4 and static(B=2, S=1 << 20, Hq=2, Hkv=2) == -4   # beyond the static array
 
 
+    def fwd_sp(x=one, o=one, lse=one, B=1, Sl=256, Hq=8, Hkv=8, D=128, P=4, scale=0.1, causal=1):
+        return lib.ie_attn_fwd_sp(x, o, lse, B, Sl, Hq, Hkv, D, P, scale, causal, None)
+
+    assert fwd_sp(x=None) == -1 and fwd_sp(lse=None) == -1
+    assert fwd_sp(P=3) == -2 and fwd_sp(P=0) == -2 and fwd_sp(Sl=0) == -2 and fwd_sp(Hkv=6) == -2
+    assert fwd_sp(Sl=128) == -3 and fwd_sp(Sl=384) == -3 and fwd_sp(D=96) == -3
+    assert fwd_sp(x=ctypes.c_void_p(264)) == -6
+
+    def bwd_sp(ws=one, ws_bytes=1 << 30, dx=one, **kw):
+        a = dict(B=1, Sl=256, Hq=8, Hkv=8, D=128, P=4, scale=0.1, causal=1)
+        a.update(kw)
+        return lib.ie_attn_bwd_sp(one, one, one, one, dx, a["B"], a["Sl"], a["Hq"], a["Hkv"], a["D"], a["P"], a["scale"],
+                                  a["causal"], ws, ws_bytes, None)
+
+    assert bwd_sp(dx=None) == -1 and bwd_sp(P=3) == -2 and bwd_sp(Sl=300) == -3
+    assert bwd_sp(ws=None) == -4 and bwd_sp(ws_bytes=64) == -4
+
+
 def test_permute_bad_arguments_fail_before_any_launch(lib):
     one, odd = ctypes.c_void_p(256), ctypes.c_void_p(264)   # never dereferenced
     ok = dict(B=2, Sl=128, Hq=8, Hkv=4, D=128, P=4)
