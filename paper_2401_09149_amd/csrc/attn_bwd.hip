@@ -80,18 +80,26 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_delta_kernel(AttnParams p) 
 }
 
 // ---- dQ ----------------------------------------------------------------------------------
-// Same skeleton as the forward kernel: 128 query rows per workgroup (32 per wave, Q and dO
-// fragments in registers), 64-key K/V tiles double-buffered in LDS by asynchronous copies,
-// each consumed as two 32-key blocks.
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) {
-  constexpr int BM = 128, BN = 64;
+// Same skeleton as the narrow forward kernel: 32 query rows per wave (Q and dO fragments in registers), 64-key K/V
+// tiles double-buffered in LDS by asynchronous copies, each consumed as two 32-key blocks.  WAVES = 4: 128 query rows
+// per workgroup, two workgroups per CU.  WAVES = 8: 256 query rows per workgroup, one workgroup per CU with two waves
+// per SIMD, so that every K/V tile is copied into LDS once per 256 queries instead of once per 128.
+template <int WAVES>
+struct DqCfg {
+  static constexpr int THREADS = 64 * WAVES;
+  static constexpr int BM = 32 * WAVES;
+  static constexpr int BN = 64;   // keys per LDS stage (128-key stages were 2 % slower with either workgroup size)
+  template <int D> static constexpr int smem_bytes() { return 2 * 2 * BN * D * 2; }   // two stages of a K and a V tile
+};
+template <int D, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void attn_bwd_dq_kernel(AttnParams p) {
+  constexpr int BM = DqCfg<WAVES>::BM, BN = DqCfg<WAVES>::BN, THREADS = DqCfg<WAVES>::THREADS;
   constexpr int NKS = D / 16, NDB = D / 32;
   constexpr int TILE_BYTES = BN * D * 2;
   constexpr int STAGE_BYTES = 2 * TILE_BYTES;
   constexpr int ROW_BYTES = D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  __shared__ int scratch[8];
+  __shared__ int scratch[2 * WAVES + 2];
 
   __shared__ QueueState s_work;
   queue_init(p, &s_work);
@@ -107,13 +115,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   const int lane = tid & 63, wv = tid >> 6;
   const int n = lane & 31, h = lane >> 5, grp = lane >> 4;
 
-  TileCoord tc = decode_tile<BM>(p, p.Hq, true, scratch, item, tid);
+  TileCoord tc = decode_tile<BM, THREADS>(p, p.Hq, true, scratch, item, tid);
   if (!tc.valid) continue;
+  // (the tile coordinates may have come through LDS: wave-uniform values are moved to scalar registers explicitly)
   const int g = tc.h / (p.Hq / p.Hkv);
-  const int64_t q0 = tc.t0;
-  const int64_t q_end = (q0 + BM < tc.doc_end) ? q0 + BM : tc.doc_end;
-  const int64_t k_begin = tc.doc_begin;
-  const int64_t k_end = p.causal ? q_end : tc.doc_end;
+  const int64_t q0 = uniform(tc.t0), doc_end = uniform(tc.doc_end);
+  const int64_t q_end = (q0 + BM < doc_end) ? q0 + BM : doc_end;
+  const int64_t k_begin = uniform(tc.doc_begin);
+  const int64_t k_end = p.causal ? q_end : doc_end;
   const int nk = (int)(k_end - k_begin);
   const int nkt = (nk + BN - 1) / BN;
   const int nfull = nk / BN;
@@ -121,22 +130,39 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   const int64_t q_stride = (int64_t)p.Hq * D;
   const int64_t kv_pitch = (int64_t)p.Hkv * D * 2;
   const int64_t qhead = ((int64_t)tc.b * p.S * p.Hq + tc.h) * D;   // for dout (always contiguous)
-  // (wave-uniform values that came through LDS are moved to scalar registers explicitly)
   const char* kbase = uniform(reinterpret_cast<const char*>(p.k + g * D) + tc.b * p.kv_bstride);   // key tile kt starts at token k_begin + kt * BN
   const char* vbase = uniform(reinterpret_cast<const char*>(p.v + g * D) + tc.b * p.kv_bstride);
-  const int64_t k_begin_u = uniform(k_begin);
-  auto key_tile_off = [&](const int kt) __attribute__((always_inline)) { return tok_off(p, k_begin_u + (int64_t)kt * BN, kv_pitch); };
+  auto key_tile_off = [&](const int kt) __attribute__((always_inline)) { return tok_off(p, k_begin + (int64_t)kt * BN, kv_pitch); };
 
   const uint32_t lds0 = lds_address(smem);
-  AsyncTile<D> ld;
+  AsyncTile<D, WAVES> ld;
   ld.init(tid, kv_pitch);
-  ld.load(lds0, kbase + key_tile_off(0), nk);
-  ld.load(lds0 + TILE_BYTES, vbase + key_tile_off(0), nk);
+  // Asynchronous copy of key tile kt, of which `rows` >= 1 rows exist, into the stage at LDS address `lds`, in
+  // 64-row parts; a part that lies past the end repeats the last valid row (masked later).
+  auto load_kv = [&](const uint32_t lds, const int kt, const int rows, auto full) __attribute__((always_inline)) {
+    const int64_t off = key_tile_off(kt);
+#pragma unroll
+    for (int part = 0; part < BN / 64; ++part) {
+      const uint32_t dst = lds + part * 64 * ROW_BYTES;
+      if (full) {
+        ld.load_full(dst, kbase + off + (int64_t)(64 * part) * kv_pitch);
+        ld.load_full(dst + TILE_BYTES, vbase + off + (int64_t)(64 * part) * kv_pitch);
+      } else {
+        const int first = rows > 64 * part ? 64 * part : rows - 1;
+        const int valid = rows > 64 * part ? rows - 64 * part : 1;
+        ld.load(dst, kbase + off + (int64_t)first * kv_pitch, valid);
+        ld.load(dst + TILE_BYTES, vbase + off + (int64_t)first * kv_pitch, valid);
+      }
+    }
+  };
+  load_kv(lds0, 0, nk, std::false_type{});
 
-  int64_t row = q0 + wv * 32 + n;
-  const bool row_ok = row < q_end;
-  if (!row_ok) row = q_end - 1;
-  const int row_rel = (int)(row - k_begin);
+  // This lane's query row, as a 32-bit position inside the document (rows past the tile's end repeat its last row and
+  // are not written).
+  const int rows_rel_end = (int)(q_end - k_begin);
+  const int row_rel_raw = (int)(q0 - k_begin) + wv * 32 + n;
+  const int row_rel = row_rel_raw < rows_rel_end ? row_rel_raw : rows_rel_end - 1;
+  const int64_t row = k_begin + row_rel;
 
   bf16x8 qf[NKS], dof[NKS];
 #pragma unroll
@@ -177,18 +203,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
   auto tile_step = [&](const int kt, const int stage, auto full_next) __attribute__((always_inline)) {
     const int kb = kt * BN;
     const uint32_t next_lds = lds0 + (STAGE_BYTES - stage);
-    if (full_next) {
-      ld.load_full(next_lds, kbase + key_tile_off(kt + 1));
-      ld.load_full(next_lds + TILE_BYTES, vbase + key_tile_off(kt + 1));
-    } else if (kt + 1 < nkt) {
-      ld.load(next_lds, kbase + key_tile_off(kt + 1), nk - kb - BN);
-      ld.load(next_lds + TILE_BYTES, vbase + key_tile_off(kt + 1), nk - kb - BN);
-    }
+    if (full_next) load_kv(next_lds, kt + 1, BN, std::true_type{});
+    else if (kt + 1 < nkt) load_kv(next_lds, kt + 1, nk - kb - BN, std::false_type{});
     const bool need_mask = (p.causal && kb + BN - 1 > wave_row_min) || (kb + BN > nk);
     const int lim = (p.causal ? row_rel : nk - 1) - kb - 4 * h;
 
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < BN / 32; ++j) {
       const int blk = stage + 32 * j * ROW_BYTES;
       f32x16 s, dp;
 #pragma unroll
@@ -252,10 +273,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(AttnParams p) 
 
   // (the row is formed again from its 32-bit position: a 64-bit row index kept alive through the main loop is two
   // registers this kernel does not have)
+  int row_rel_late = row_rel;
+  asm volatile("" : "+v"(row_rel_late));   // (opaque: otherwise the address is formed in the prologue all the same)
   __bf16* drow = reinterpret_cast<__bf16*>(reinterpret_cast<char*>(p.dq + tc.h * D) + tc.b * p.q_bstride +
-                                           tok_off(p, k_begin_u + row_rel, q_stride * 2));
+                                           tok_off(p, k_begin + row_rel_late, q_stride * 2));
 #pragma unroll
-  for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc[db], p.scale, h, row_ok);
+  for (int db = 0; db < NDB; ++db) store_block32_bf16(drow + 32 * db, acc[db], p.scale, h, wave_row_min + n < rows_rel_end);
   }  // next item
 }
 
@@ -907,6 +930,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_from_ds_kernel(AttnPa
 
 // Work-queue counters of the two main kernels inside the workspace's counter area (in 4-byte units).
 constexpr int kCountersDq = 0, kCountersDkdv = kQueueBytes / 4;
+constexpr int kDqWaves = 8;   // waves per workgroup of the recomputing dQ kernel at head dimension 128 (four: 2 % slower)
 
 template <int D>
 static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
@@ -944,14 +968,18 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
         return 0;
       }
     }
-    constexpr int smem = 2 * 2 * 64 * D * 2;
+    constexpr int W = D == 128 ? kDqWaves : 4;
+    constexpr int smem = DqCfg<W>::template smem_bytes<D>();
     static KernelSetup setup;
     int per_cu = 1;
-    int rc = kernel_setup(setup, attn_bwd_dq_kernel<D>, smem, &per_cu);
+    int rc = kernel_setup(setup, attn_bwd_dq_kernel<D, W>, smem, &per_cu, 64 * W);
     if (rc) return rc;
+    tiles = tiles_per_head(p.S, DqCfg<W>::BM, p.cu, p.num_docs);
+    items = tiles * p.B * p.Hq;
+    a.tiles = (int32_t)tiles;
     const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st);
     if (ql.err != hipSuccess) return hip_fail(ql.err);
-    attn_bwd_dq_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
+    attn_bwd_dq_kernel<D, W><<<dim3((unsigned)ql.grid), dim3(64 * W), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
     return 0;
   };

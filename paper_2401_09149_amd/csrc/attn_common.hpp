@@ -333,12 +333,12 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {  // LDS byte ad
   return (uint32_t)(uintptr_t)p;
 }
 
-template <int D>
+template <int D, int WAVES = 4>
 struct AsyncTile {
   static constexpr int CPR = D / 8;          // 16-byte chunks per row
   static constexpr int RPI = 64 / CPR;       // rows per wave instruction
-  static constexpr int NI = 64 / RPI / 4;    // instructions per wave per tile
-  int row0;             // row this lane fetches in instruction 0 (instruction i adds 4 * RPI * i)
+  static constexpr int NI = 64 / RPI / WAVES;  // instructions per wave per tile
+  int row0;             // row this lane fetches in instruction 0 (instruction i adds WAVES * RPI * i)
   uint32_t chunk_byte;  // byte offset of its logical chunk inside the row
   uint32_t voff;        // row0 * pitch + chunk_byte
   uint32_t pitch;       // bytes between consecutive rows (< 2^24)
@@ -348,7 +348,8 @@ struct AsyncTile {
     const int lane = tid & 63;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     row0 = wave * RPI + lane / CPR;
-    chunk_byte = ((lane % CPR) ^ swz<D>(row0)) << 4;  // swz depends on row & 15 only; 4*RPI*i is a multiple of 16
+    static_assert((WAVES * RPI) % 16 == 0, "the swizzle of a lane's row must not change from one instruction to the next");
+    chunk_byte = ((lane % CPR) ^ swz<D>(row0)) << 4;  // swz depends on row & 15 only; WAVES*RPI*i is a multiple of 16
     pitch = (uint32_t)pitch_bytes;
     voff = (uint32_t)row0 * pitch + chunk_byte;
   }
@@ -361,16 +362,16 @@ struct AsyncTile {
   // One of the NI instructions of load_full, for callers that spread them over their arithmetic
   // (a wave issues in order, and the memory pipeline accepts about 1 KiB per 16 cycles per CU).
   __device__ __forceinline__ void load_full_piece(uint32_t lds, const char* g, int i) const {
-    async_copy16(voff, g + (uint64_t)(4 * RPI * i) * pitch, lds + (i * 4 + wave) * 1024);
+    async_copy16(voff, g + (uint64_t)(WAVES * RPI * i) * pitch, lds + (i * WAVES + wave) * 1024);
   }
   // Same when only rows [0, rows_valid) exist: later rows repeat row rows_valid-1 so that no
   // load leaves the tensor (their values are masked by the caller).  1 <= rows_valid <= 64.
   __device__ __forceinline__ void load_partial(uint32_t lds, const char* g, int rows_valid) const {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      int r = row0 + 4 * RPI * i;
+      int r = row0 + WAVES * RPI * i;
       r = r < rows_valid ? r : rows_valid - 1;
-      async_copy16((uint32_t)r * pitch + chunk_byte, g, lds + (i * 4 + wave) * 1024);
+      async_copy16((uint32_t)r * pitch + chunk_byte, g, lds + (i * WAVES + wave) * 1024);
     }
   }
   __device__ __forceinline__ void load(uint32_t lds, const char* g, int rows_valid) const {
@@ -427,8 +428,10 @@ struct TileCoord {
 // workgroup does).  Otherwise (B*H not a multiple of 8) there is one list and heads simply
 // alternate (head = w % (B*H)).  `heavy_last` says whether high tile numbers carry the most work
 // (forward and dq: causal rows late in a document see more keys).
-template <int TS>
+// `scratch`: 2 * THREADS / 64 + 2 ints of LDS (THREADS = workgroup size).
+template <int TS, int THREADS = kThreads>
 __device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads, bool heavy_last, int* scratch, int w, int tid) {
+  constexpr int NW = THREADS / 64;
   TileCoord c;
   // (the divisors below are the same for every item of a launch; they are made opaque so that a persistent kernel
   // does not compute their reciprocals ahead of its item loop and keep them in registers through it)
@@ -461,12 +464,12 @@ __device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads,
   // (`tid` is the caller's copy of the thread index: persistent kernels pass an opaque one, so that nothing
   // below is computed ahead of their item loop and kept in registers through it)
   int lane = tid & 63, wv = tid >> 6;
-  int* s_wave = scratch;       // [4] wave totals
-  int* s_res = scratch + 4;    // [0] doc index or -1, [1] tiles before that doc
+  int* s_wave = scratch;       // [NW] wave totals
+  int* s_res = scratch + NW;   // [0] doc index or -1, [1] tiles before that doc
   if (tid == 0) { s_res[0] = -1; s_res[1] = 0; }
   __syncthreads();
   int before = 0;  // tiles of all documents in earlier rounds
-  for (int base = 0; base < p.num_docs; base += kThreads) {
+  for (int base = 0; base < p.num_docs; base += THREADS) {
     int d = base + tid;
     int nt = 0;
     if (d < p.num_docs) nt = (p.cu[d + 1] - p.cu[d] + TS - 1) / TS;
@@ -480,7 +483,7 @@ __device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads,
     __syncthreads();
     int woff = 0, total = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { int x = s_wave[i]; if (i < wv) woff += x; total += x; }
+    for (int i = 0; i < NW; ++i) { int x = s_wave[i]; if (i < wv) woff += x; total += x; }
     int excl = before + woff + inc - nt;
     if (nt > 0 && t >= excl && t < excl + nt) { s_res[0] = d; s_res[1] = excl; }
     __syncthreads();

@@ -73,7 +73,7 @@ __device__ __forceinline__ int next_work(const AttnParams& p, QueueState* s_work
 // that fit on one CU together (registers, LDS; at least 1) is asked once.
 struct KernelSetup { std::atomic<int> per_cu[kMaxDevices]; };
 template <typename K>
-static inline int kernel_setup(KernelSetup& ks, K kernel, int smem_bytes, int* per_cu) {
+static inline int kernel_setup(KernelSetup& ks, K kernel, int smem_bytes, int* per_cu, int threads = kThreads) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return hip_fail(e);
@@ -81,7 +81,7 @@ static inline int kernel_setup(KernelSetup& ks, K kernel, int smem_bytes, int* p
   if (n == 0) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes);
     if (e != hipSuccess) return hip_fail(e);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(kernel), kThreads, (size_t)smem_bytes) != hipSuccess || n < 1) n = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(kernel), threads, (size_t)smem_bytes) != hipSuccess || n < 1) n = 1;
     if (dev < kMaxDevices) ks.per_cu[dev].store(n, std::memory_order_release);
   }
   *per_cu = n;
