@@ -329,8 +329,16 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
 
   TileCoord tc = decode_tile<BK>(p, p.Hkv, false, scratch, item, tid);
   if (!tc.valid) continue;
+  // The tile coordinates may have come through LDS (packed input): they are the same in every lane, and are moved
+  // to scalar registers here so that everything derived from them between two steps (the description of the next
+  // query tile: three 64-bit addresses) is scalar arithmetic instead of vector multiplies and lane reads.
+  tc.b = (int)uniform((uint32_t)tc.b);
+  tc.h = (int)uniform((uint32_t)tc.h);
+  tc.t0 = uniform(tc.t0);
+  tc.doc_begin = uniform(tc.doc_begin);
+  tc.doc_end = uniform(tc.doc_end);
   const int g = tc.h;
-  const int group = p.Hq / p.Hkv;
+  const int group = (int)uniform((uint32_t)(p.Hq / p.Hkv));   // (an integer division leaves its result in a vector register)
   const int64_t k0 = tc.t0;
   const int64_t q_begin = p.causal ? k0 : tc.doc_begin;
   const int nq = (int)(tc.doc_end - q_begin);  // query rows that can see this key tile
@@ -490,8 +498,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   // Every operand group is requested a phase before the phase that consumes it and one or two
   // reads per MFMA, never in a burst (a wave issues in order).  X(0) has no dK (the previous
   // block's was issued in the prologue) and the last Y no S.
-  auto fast_tile = [&](const StagePtrs& sp_, const TileCopy& next, auto spread_copies) __attribute__((always_inline)) {
+  // `make_next` describes the next tile (address arithmetic, all scalar); it is called behind the tile's first MFMAs,
+  // which hide it: in front of them, right after the step's barrier, the matrix pipeline would wait for it.
+  auto fast_tile = [&](const StagePtrs& sp_, auto make_next, auto spread_copies) __attribute__((always_inline)) {
     constexpr bool kSpread = decltype(spread_copies)::value;  // copy the next tile piece by piece between the chains
+    TileCopy next;   // (described behind the first MFMAs, see below)
     static_assert(NDB == 4 || NDB == 2, "the schedule below is written for D = 128 (used) and only has to compile for 64");
     bf16x8 qn[NKS], don[NKS], dotf[2][NDB];
     f32x16 s, dp, nl, nd;   // nl: -lse*log2e of the rows of s; nd: -delta of the rows of the next dP chain
@@ -550,6 +561,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
       if (ks == 0) mfma_first_b_agpr(s, qn[0], kf[0]);
       else mfma_next_b_agpr(s, qn[ks], kf[ks]);
     }
+    asm_fence();
+    if (kSpread) next = make_next();
     asm_fence();
 
 #pragma unroll
@@ -732,17 +745,23 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
     int next_hq = hq_idx, next_tile = tile_idx + 1;
     if (next_tile == nqt) { next_tile = 0; ++next_hq; }
     const bool has_next = st + 1 < total;
-    const TileCopy next = describe(has_next ? next_hq : hq_idx, has_next ? next_tile : tile_idx, 1 - slot);
-    const bool next_full = has_next && next.rows >= BQ;
+    auto make_next = [&]() __attribute__((always_inline)) {
+      // (the tile number is made opaque HERE: whatever depends on it is then computed behind the assembly statements
+      // that precede the call, not hoisted in front of them)
+      int t_next = has_next ? next_tile : tile_idx;
+      asm volatile("" : "+s"(t_next));
+      return describe(has_next ? next_hq : hq_idx, t_next, 1 - slot);
+    };
+    const bool next_full = has_next && nq - next_tile * BQ >= BQ;
     const int i0 = tile_idx * BQ;
     // Mask when a key of this wave can exceed a row of the tile (causal) or rows run past the document.
     const bool need_mask = (p.causal && wv * 32 + 31 > i0) || (i0 + BQ > nq);
     const bool fast = D == 128 && !need_mask;
     if (fast && next_full) {
-      fast_tile(sp[slot], next, std::true_type{});
+      fast_tile(sp[slot], make_next, std::true_type{});
     } else {
-      if (has_next) copy_all(next);
-      if (fast) fast_tile(sp[slot], next, std::false_type{});
+      if (has_next) copy_all(make_next());
+      if (fast) fast_tile(sp[slot], make_next, std::false_type{});
       else generic_tile(sp[slot], i0);
     }
     // The next tile's copies have landed; vector memory operations complete in issue order, and after a
