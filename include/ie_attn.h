@@ -22,15 +22,19 @@
  *
  * Common conventions
  *   - Every pointer is a DEVICE pointer on the current HIP device; the caller owns all
- *     buffers.  The library allocates nothing and never synchronises with the host (its only state is a
- *     small device array of work-queue counters that every launch clears for itself on `stream`): all
+ *     buffers.  The library allocates no device memory and never synchronises with the host: all
  *     work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and the buffers must stay alive until the stream has passed it.
- *     Calls may overlap on different streams; each launch takes the next of 256 counter slots, so
- *     more than 256 launches of one kernel in flight at once would share one.
+ *     Calls may overlap on different streams.  The kernels are persistent and draw their work from eight
+ *     counters per launch, which a one-wave kernel clears on `stream` in front of the main kernel.  The
+ *     backward kernels keep them in the caller's workspace: two backward calls that overlap must not share a
+ *     workspace.  ie_attn_fwd (head dimension 128) takes them from 256 slots of a device array inside the
+ *     library; a slot is handed out again only when the event recorded behind its previous launch has
+ *     completed, or to a launch on the same stream, and when every slot is in flight on other streams the
+ *     call returns IE_ERR_BUSY rather than share one.
  *     A call enqueues kernel launches only (no memset, no copy, no allocation), so it may be recorded
- *     under stream capture; the counter slot is then fixed in the graph, and two replays of the same
- *     graph must not run at the same time.
+ *     under stream capture; a forward call captured into a graph keeps its counter slot for the life of
+ *     the process (at most 256 such calls), and two replays of one graph must not run at the same time.
  *   - q, o, dout, dq : contiguous [B, S, Hq,  D] bf16.
  *     k, v, dk, dv   : contiguous [B, S, Hkv, D] bf16.
  *     lse            : contiguous [B, Hq, S] fp32, natural log, `scale` included.
@@ -78,21 +82,24 @@ int ie_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
                 float scale, int32_t causal, void* stream);
 
 /*
- * Bytes of device workspace ie_attn_bwd needs for this shape (it holds -delta and
- * -lse * log2(e), [B,Hq,S] fp32 each, between the kernels of one call).  Returns 0 for an invalid shape.  Pure host
- * arithmetic; touches no device.
+ * Bytes of device workspace ie_attn_bwd needs for this shape: 8 * B * Hq * S (rounded up) + 256.  It holds -delta and
+ * -lse * log2(e), [B,Hq,S] fp32 each, between the kernels of one call, and their work-queue counters: memory that
+ * grows with S, not S^2, which is what the fused kernel is in the method for (Sec. 3.2; Sec. 2.4 "SP-3").  Returns 0
+ * for an invalid shape.  Pure host arithmetic; touches no device.
  */
 size_t ie_attn_bwd_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs);
 
 /*
- * Bytes of workspace with which ie_attn_bwd trades memory for matrix work.  For dense input (num_docs == 0) with
+ * Bytes of workspace of the OPTIONAL backward path that trades memory for matrix work (selected with IE_BWD_STORED_DS
+ * in ie_attn_bwd_phases, never by the size of the workspace alone).  For dense input (num_docs == 0) with
  * D == 128 and S a multiple of 128 this is ie_attn_bwd_workspace_bytes(...) plus room for dS = P o (dP - delta) in
- * bf16: B * Hq * S * (S + 128) bytes when causal (the lower block triangle of every head), 2 * B * Hq * S * S otherwise.
- * Given that much, the dK/dV kernel stores the dS it forms and dQ = scale * dS K is computed from it, instead of
+ * bf16: B * Hq * S * (S + 128) bytes when causal (the lower block triangle of every head), 2 * B * Hq * S * S otherwise
+ * (34.5 GB at B=1, S=32768, Hq=32).
+ * On that path the dK/dV kernel stores the dS it forms and dQ = scale * dS K is computed from it, instead of
  * recomputing S, P and dP a second time for dQ (five matrix products per block pair instead of seven; the appendix "Implementation Detail: Selective Overlap" counts
  * the backward pass as the compute-heavier direction).  The results differ from the recomputing path only in
  * summation order (same bf16 dS, fp32 accumulation).  For every other shape the function returns
- * ie_attn_bwd_workspace_bytes(...): there is no such path and a larger workspace changes nothing.  Pure host arithmetic.
+ * ie_attn_bwd_workspace_bytes(...): there is no such path.  Pure host arithmetic.
  */
 size_t ie_attn_bwd_fast_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t num_docs,
                                         int32_t causal);
@@ -103,8 +110,7 @@ size_t ie_attn_bwd_fast_workspace_bytes(int64_t B, int64_t S, int32_t Hq, int32_
  * probabilities are recomputed from lse (Sec. 3.2), backward costs 2.5x the forward's
  * matrix work (cf. the appendix "Implementation Detail: Selective Overlap": backward is about twice as compute-intensive as forward).
  * `workspace` is caller-owned scratch of at least ie_attn_bwd_workspace_bytes(...) bytes,
- * 256-byte aligned; its contents after the call are unspecified.  With at least
- * ie_attn_bwd_fast_workspace_bytes(...) bytes the dS-storing path described there is taken.  Every output element
+ * 256-byte aligned; its contents after the call are unspecified; a larger workspace changes nothing.  Every output element
  * has a single owner and a fixed summation order, so results are bitwise reproducible.
  */
 int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -119,9 +125,11 @@ int ie_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
  * that time one kernel at a time.  `phases` is a bit mask: IE_BWD_DELTA (delta = rowsum(dO o O)
  * and lse * log2(e), both negated, into the workspace), IE_BWD_DQ (writes dq; needs what IE_BWD_DELTA left in the
  * workspace), IE_BWD_DKDV (writes dk and dv; needs the same).  Outputs of phases that are not selected are left
- * untouched.  On the dS-storing path (ie_attn_bwd_fast_workspace_bytes) IE_BWD_DKDV also leaves dS in the workspace
- * and IE_BWD_DQ needs it: run IE_BWD_DKDV before IE_BWD_DQ there.  ie_attn_bwd(...) is ie_attn_bwd_phases(..., IE_BWD_ALL).  A mask of 0 or with
- * other bits set is IE_ERR_UNSUPPORTED.
+ * untouched.  ie_attn_bwd(...) is ie_attn_bwd_phases(..., IE_BWD_ALL).
+ * IE_BWD_STORED_DS, or-ed into the mask, selects the dS-storing path: the workspace must then have
+ * ie_attn_bwd_fast_workspace_bytes(...) bytes (IE_ERR_WORKSPACE otherwise) and the shape must have that path
+ * (IE_ERR_UNSUPPORTED otherwise).  There IE_BWD_DKDV also leaves dS in the workspace and IE_BWD_DQ needs it: run
+ * IE_BWD_DKDV before IE_BWD_DQ.  A mask without a phase bit or with other bits set is IE_ERR_UNSUPPORTED.
  */
 enum { IE_BWD_DELTA = 1, IE_BWD_DQ = 2, IE_BWD_DKDV = 4, IE_BWD_ALL = 7, IE_BWD_STORED_DS = 16 };
 int ie_attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* dout,
