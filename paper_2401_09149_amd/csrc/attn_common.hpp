@@ -46,7 +46,7 @@ struct AttnParams {
   float scale, scale_log2;  // scale_log2 = scale * log2(e)
   int32_t causal;
   int32_t tiles;            // tiles per head the grid was sized for (upper bound when packed)
-  int32_t q_reserved, q_per_xcd, q_total;  // persistent launches (tile_queue.hpp): items per XCD list (0: one list), items
+  int32_t q_heavy, q_per_xcd, q_total;  // persistent launches (tile_queue.hpp): tiles per head in a list's head-by-head part, items per XCD list (0: one list), items
   __bf16* ds;               // optional workspace: dS written by the dK/dV kernel for the dQ kernel (see ds_matrix_offset), or NULL
   // Where token t of batch entry b lives in q/dq (pitch Hq*D) and k/v/dk/dv (pitch Hkv*D), see tok_off():
   // contiguous [B,S,heads,D] tensors, or the chunks of a sequence-parallel exchange buffer (one chunk per peer).
@@ -442,7 +442,7 @@ __device__ __forceinline__ TileCoord decode_tile(const AttnParams& p, int heads,
   if (nH % 8 == 0) {
     const int xcd = w & 7, slot = w >> 3;
     const int hpx = opaque(nH / 8);                        // heads per list
-    const int heavy = opaque(p.tiles - p.tiles * 3 / 8);   // tiles per head in the head-by-head part
+    const int heavy = opaque(p.q_heavy);                   // tiles per head in the head-by-head part
     if (slot < heavy * hpx) { hh = xcd + 8 * (slot / heavy); t = slot % heavy; }
     else { const int r = slot - heavy * hpx; hh = xcd + 8 * (r % hpx); t = heavy + r / hpx; }
   } else {
