@@ -566,6 +566,9 @@ int slot_acquire(hipStream_t st, int* dev_out, int* slot_out, unsigned int** cou
     if ((e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_fwd_queue))) != hipSuccess) return hip_fail(e);
     pool.base = static_cast<unsigned int*>(ptr);
   }
+  // (querying an event is not allowed while this thread captures in the default mode: relax the mode around it)
+  hipStreamCaptureMode mode = hipStreamCaptureModeRelaxed;
+  if (*capturing && (e = hipThreadExchangeStreamCaptureMode(&mode)) != hipSuccess) return hip_fail(e);
   int found = -1;
   for (int i = 0; i < kFwdSlots && found < 0; ++i) {
     const int s = (pool.next + i) % kFwdSlots;
@@ -576,6 +579,7 @@ int slot_acquire(hipStream_t st, int* dev_out, int* slot_out, unsigned int** cou
     }
     if (pool.state[s] == kSlotFree) found = s;
   }
+  if (*capturing) (void)hipThreadExchangeStreamCaptureMode(&mode);
   // nothing has completed: a slot whose launch sits earlier on this very stream is as good
   for (int i = 0; i < kFwdSlots && found < 0 && !*capturing; ++i) {
     const int s = (pool.next + i) % kFwdSlots;

@@ -197,6 +197,39 @@ def test_overlapping_launches_on_two_streams_and_many_launches_in_a_row():
         assert torch.equal(got, want)
 
 
+def test_forward_never_shares_a_work_queue_slot():
+    """More forward launches in flight on DIFFERENT streams than the library has work-queue slots (256): every call
+    either succeeds, and then its result is right, or fails with IE_ERR_BUSY before launching anything; no call
+    silently shares counters with a launch that is still running.  Afterwards the slots come back."""
+    import torch
+    from paper_2401_09149_amd import binding
+    dev = "cuda:0"
+    B, S, Hq, Hkv, D = 1, 32768, 16, 16, 128          # about 4 ms per launch: the first ones are still running
+    scale = D ** -0.5                                  # when the 257th is issued
+    q, k, v = (randn_bf16((B, S, H, D), 171 + j).to(dev) for j, H in enumerate((Hq, Hkv, Hkv)))
+    o_ref, lse_ref = binding.attn_fwd(q, k, v, scale, True, None)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(300)]
+    # (all launches write the same values to one pair of buffers: a launch that went wrong leaves its mark all the same)
+    o = torch.empty_like(o_ref)
+    lse = torch.empty_like(lse_ref)
+    accepted = busy = 0
+    for st in streams:
+        try:
+            binding.ie_attn_fwd(q, k, v, o, lse, None, scale, True, stream=st)
+            accepted += 1
+        except binding.IeAttnError as e:
+            assert e.code == -7, e
+            busy += 1
+    torch.cuda.synchronize()
+    print(f"  {accepted} launches accepted, {busy} refused with IE_ERR_BUSY", flush=True)
+    assert accepted >= 256
+    assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+    o, lse = binding.attn_fwd(q, k, v, scale, True, None)   # everything has completed: slots are free again
+    torch.cuda.synchronize()
+    assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+
+
 def test_autograd_wrapper_gives_the_same_gradients():
     import torch
     from paper_2401_09149_amd import binding

@@ -13,6 +13,7 @@ pytestmark = pytest.mark.gpu
     (1, 1024, 4, 4, 128, 4, False),    # not causal
     (2, 256, 4, 2, 64, 2, True),       # head dimension 64 (the other forward kernel)
     (1, 2048, 16, 16, 128, 8, True),   # two local heads, eight peers
+    (1, 8192, 32, 32, 128, 4, True),   # the paper's own plan for 7B at 32K (s_sp = 4: 8 heads per GPU), full size
 ])
 def test_fused_calls_equal_unpack_attention_pack(B, Sl, Hq, Hkv, D, P, causal):
     import torch
