@@ -178,6 +178,20 @@ int ie_attn_bwd_static(const void* q, const void* k, const void* v, const void* 
                        int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
                        float scale, int32_t causal, void* stream);
 
+/*
+ * Query rows per work item at head dimension 128, for the forward and the recomputing dQ kernel: 256
+ * (one persistent workgroup per CU; the faster steady state) or 128 (two workgroups per CU; half the
+ * work per item, which wins when a launch has few items per CU or the sequence is short).  rows = 0
+ * (the initial setting) lets every call choose from its shape: dense input of up to 4096 tokens, or
+ * up to 8192 tokens with fewer than two 256-row items per CU, takes the 128-row forward; dense input
+ * of 8192 tokens or more with fewer than two 256-row items per CU takes the 128-row dQ.  rows = 128
+ * or 256 fixes the choice for all later calls of the process (measurements, tests); the results of
+ * the two differ only in rounding order.  Returns the previous setting, or IE_ERR_UNSUPPORTED for any
+ * other value.  Head dimension 64 always works on 128-row items.  (Sec. 4.2: self-atten is profiled
+ * over shapes from 4K x 40 heads to 256K x 1 head per GPU.)
+ */
+int ie_attn_set_tile_rows(int32_t rows);
+
 /* Static text for a status code (never NULL). */
 const char* ie_attn_strerror(int code);
 

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("IE_ATTN_LIB") or os.path.join(_HERE, "libie_attn.so")  # override: for trying out a build
 
 EXPORTS = ("ie_attn_fwd", "ie_attn_bwd_workspace_bytes", "ie_attn_bwd_fast_workspace_bytes", "ie_attn_bwd", "ie_attn_bwd_phases",
-           "ie_attn_bwd_static", "ie_attn_fwd_sp", "ie_attn_bwd_sp", "ie_attn_strerror",
+           "ie_attn_bwd_static", "ie_attn_fwd_sp", "ie_attn_bwd_sp", "ie_attn_set_tile_rows", "ie_attn_strerror",
            "ie_attn_last_hip_error",
            "ie_sp_pack_qkv", "ie_sp_unpack_qkv", "ie_sp_pack_o", "ie_sp_unpack_o",
            "ie_sp_pack_do", "ie_sp_unpack_do", "ie_sp_pack_dqkv", "ie_sp_unpack_dqkv",
@@ -54,6 +54,7 @@ def load():
     lib.ie_attn_fwd_sp.restype = ctypes.c_int
     lib.ie_attn_bwd_sp.argtypes = [vp] * 5 + [i64, i64, i32, i32, i32, i32, f32, i32, vp, ctypes.c_size_t, vp]
     lib.ie_attn_bwd_sp.restype = ctypes.c_int
+    lib.ie_attn_set_tile_rows.argtypes = [i32]
     lib.ie_attn_strerror.argtypes = [ctypes.c_int]
     lib.ie_attn_strerror.restype = ctypes.c_char_p
     lib.ie_attn_last_hip_error.argtypes = []
@@ -70,6 +71,14 @@ def load():
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
+
+
+def ie_attn_set_tile_rows(rows):
+    """Query rows per work item at head dimension 128 (0 = chosen per call, 128, 256); returns the previous setting."""
+    prev = load().ie_attn_set_tile_rows(int(rows))
+    if prev < 0:
+        _raise(prev)
+    return prev
 
 
 def ie_attn_strerror(code):

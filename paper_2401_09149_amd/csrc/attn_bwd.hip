@@ -987,20 +987,26 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
         return 0;
       }
     }
-    constexpr int W = D == 128 ? kDqWaves : 4;
-    constexpr int smem = DqCfg<W>::template smem_bytes<D>();
-    static KernelSetup setup;
-    int per_cu = 1;
-    int rc = kernel_setup(setup, attn_bwd_dq_kernel<D, W>, smem, &per_cu, 64 * W);
-    if (rc) return rc;
-    tiles = tiles_per_head(p.S, DqCfg<W>::BM, p.cu, p.num_docs);
-    items = tiles * p.B * p.Hq;
-    a.tiles = (int32_t)tiles;
-    const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st);
-    if (ql.err != hipSuccess) return hip_fail(ql.err);
-    attn_bwd_dq_kernel<D, W><<<dim3((unsigned)ql.grid), dim3(64 * W), smem, st>>>(a);
-    if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
-    return 0;
+    auto recompute = [&](auto waves_c) -> int {
+      constexpr int W = decltype(waves_c)::value;
+      constexpr int smem = DqCfg<W>::template smem_bytes<D>();
+      static KernelSetup setup;
+      int per_cu = 1;
+      int rc = kernel_setup(setup, attn_bwd_dq_kernel<D, W>, smem, &per_cu, 64 * W);
+      if (rc) return rc;
+      tiles = tiles_per_head(p.S, DqCfg<W>::BM, p.cu, p.num_docs);
+      items = tiles * p.B * p.Hq;
+      a.tiles = (int32_t)tiles;
+      const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st);
+      if (ql.err != hipSuccess) return hip_fail(ql.err);
+      attn_bwd_dq_kernel<D, W><<<dim3((unsigned)ql.grid), dim3(64 * W), smem, st>>>(a);
+      if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
+      return 0;
+    };
+    if constexpr (D == 128) {
+      if (!dq_prefers_128_rows(ceil_div(p.S, DqCfg<kDqWaves>::BM) * p.B * p.Hq, p.S, p.cu != nullptr)) return recompute(std::integral_constant<int, kDqWaves>{});
+    }
+    return recompute(std::integral_constant<int, 4>{});
   };
   auto dkdv_phase = [&](auto store_c, auto chunked_c) -> int {
     constexpr bool kStore = decltype(store_c)::value, kChunked = decltype(chunked_c)::value;

@@ -211,7 +211,7 @@ static int launch_fwd_d(AttnParams p, hipStream_t st) {
 }
 
 int launch_fwd(AttnParams p, int D, hipStream_t st) {
-  if (D == 128) return launch_fwd_wide(p, st);
+  if (D == 128 && !fwd_prefers_128_rows(ceil_div(p.S, 256) * p.B * p.Hq, p.S, p.cu != nullptr)) return launch_fwd_wide(p, st);
   return D == 64 ? launch_fwd_d<64>(p, st) : launch_fwd_d<128>(p, st);
 }
 

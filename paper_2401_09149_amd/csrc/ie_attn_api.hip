@@ -264,6 +264,11 @@ int ie_attn_bwd_sp(const void* xqkv, const void* o, const void* dout, const floa
   return ie::launch_bwd(p, D, IE_BWD_ALL, static_cast<hipStream_t>(stream));
 }
 
+int ie_attn_set_tile_rows(int32_t rows) {
+  if (rows != 0 && rows != 128 && rows != 256) return IE_ERR_UNSUPPORTED;
+  return ie::tile_rows_setting.exchange(rows, std::memory_order_relaxed);
+}
+
 const char* ie_attn_strerror(int code) {
   switch (code) {
     case IE_OK: return "success";

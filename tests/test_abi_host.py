@@ -44,6 +44,14 @@ def test_strerror_is_total(lib):
     assert len(seen) >= 9   # eight statuses + "unknown"
 
 
+def test_tile_rows_setting(lib):
+    f = lib.ie_attn_set_tile_rows
+    assert f(0) == 0          # initial setting: chosen per call
+    assert f(128) == 0 and f(256) == 128 and f(0) == 256   # returns the previous setting
+    assert f(64) == -3 and f(-1) == -3                      # IE_ERR_UNSUPPORTED, setting unchanged
+    assert f(0) == 0
+
+
 def test_workspace_query(lib):
     f = lib.ie_attn_bwd_workspace_bytes
     n = f(1, 32768, 32, 32, 128, 0)

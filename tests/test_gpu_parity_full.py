@@ -146,6 +146,27 @@ def test_plan_shape_13b_s16k_b1_h10(oracle):
     check_identities(cfg, cu, gpu_in, gpu_out)
 
 
+def test_plan_shape_65b_s8k_h8(oracle):
+    # 65B at 8K with s_sp = 8 (Appendix Table 7: 8 heads per GPU): one 256-row item per CU, so the forward and the
+    # recomputing dQ run their 128-row kernels here by the library's own choice; whole heads against the oracle
+    from paper_2401_09149_amd import workloads as W
+    cfg = W.AttnConfig("65b_s8k_h8_d128", 14, B=1, S=8192, Hq=8, Hkv=8, D=128)
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 0)
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 7)
+    check_identities(cfg, cu, gpu_in, gpu_out)
+
+
+def test_plan_shape_7b_s4k_b2_h32(oracle):
+    # 7B at 4K with micro-batch 2 and no sequence parallelism (Appendix Table 4): the 128-row forward, the 256-row dQ
+    from paper_2401_09149_amd import workloads as W
+    cfg = W.AttnConfig("7b_s4k_b2_h32_d128", 15, B=2, S=4096, Hq=32, Hkv=32, D=128)
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 0)
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 31)
+    check_identities(cfg, cu, gpu_in, gpu_out)
+
+
 def test_config2_s128k_h8(oracle):
     from paper_2401_09149_amd import workloads as W
     cfg = W.CONFIGS[2]
