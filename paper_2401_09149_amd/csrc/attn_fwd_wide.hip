@@ -372,15 +372,16 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   // masks and maxima (with the rare rescale), then the exponentials and the two PV products in
   // one region, so that the compiler can run one column block's MFMAs under the other's
   // exponentials; the next block's fragments are requested before the current block is worked on.
-  auto masked_max = [&](f32x16& s, const int lim, ColState& st, f32x16 (&o_x)[NDB]) __attribute__((always_inline)) {
+  // (returns whether the block's maximum lies above the column's reference by more than the slack)
+  auto masked_max = [&](f32x16& s, const int lim, const ColState& st, float& mx) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       if (8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
-    float mx = s[0];
+    mx = s[0];
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
     mx = halfwave_max(mx);
-    if (__builtin_amdgcn_ballot_w64(mx > st.thr) != 0) rescale(st, o_x, mx);
+    return __builtin_amdgcn_ballot_w64(mx > st.thr) != 0;
   };
   auto exps = [&](const f32x16& s, ColState& st, bf16x8 (&pf)[2]) __attribute__((always_inline)) {
 #pragma unroll
@@ -400,9 +401,17 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
 #pragma unroll
     for (int sblk = 0; sblk < 2; ++sblk)
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) o_x[db] = mfma32(vtf[sblk][db], pf[sblk], o_x[db]);
+      for (int db = 0; db < NDB; ++db) mfma_acc_agpr_after_moves(o_x[db], vtf[sblk][db], pf[sblk]);
+    // (assembly, so that the accumulators stay in AGPRs; the compiler does not know these are MFMAs and may move
+    // an accumulator right behind them: their results have to have landed)
+    mfma_result_fence();
   };
-  auto generic_tile = [&](const int T) __attribute__((always_inline)) {
+  // Blocks r_begin.. of tile T; returns NB when done.  The rescale of 64 accumulators per column block is cold code,
+  // but with it inside the block loop the compiler copies all 128 accumulators out of the AGPRs at the top of every
+  // trip; so the loop exists twice: the `lazy` form has no rescale and leaves at the first block whose reference has
+  // to move (returning its index, nothing of that block done), and the other form takes over from there.
+  auto generic_blocks = [&](const int T, const int r_begin, auto lazy_c) __attribute__((always_inline)) {
+    constexpr bool kLazy = decltype(lazy_c)::value;
     const int so = (T & 1) * TILE_BYTES;
     const int kb = T * BN;
     bf16x8 kfr[NKS], vtf[2][NDB];
@@ -424,10 +433,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
       const int key0 = kb + 32 * r;
       return r < NB && key0 < nk && !(p.causal && key0 > wave_row_min + 63);
     };
-    if (visible(0)) { load_k(0); load_v(0); }
+    if (visible(r_begin)) { load_k(r_begin); load_v(r_begin); }
+    int r = r_begin;
 #pragma unroll 1
-    for (int r = 0; r < NB; ++r) {
-      if (!visible(r)) break;
+    for (; r < NB; ++r) {
+      if (!visible(r)) return NB;
       const bool more = visible(r + 1);
       const int key0 = kb + 32 * r;  // first key of the block, relative to k_begin
       // last visible key relative to the lane's first key of the block (keys 4h.. of each 8)
@@ -439,8 +449,15 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
       if (do_a) ss_a = mfma_chain_b_in_agpr<NKS>(kfr, qa);
       ss_b = mfma_chain_b_in_agpr<NKS>(kfr, qb);
       if (more) load_k(r + 1);  // the K fragments are free again: the next block's, a block ahead of their use
-      if (do_a) masked_max(ss_a, lim_a, sa, oa);
-      masked_max(ss_b, lim_b, sb, ob);
+      float mx_a = 0.f, mx_b = 0.f;
+      const bool move_a = do_a && masked_max(ss_a, lim_a, sa, mx_a);
+      const bool move_b = masked_max(ss_b, lim_b, sb, mx_b);
+      if (kLazy) {
+        if (move_a || move_b) return r;
+      } else {
+        if (move_a) rescale(sa, oa, mx_a);
+        if (move_b) rescale(sb, ob, mx_b);
+      }
       if (do_a) {
         exps(ss_a, sa, pf_a);
         pv(oa, vtf, pf_a);
@@ -449,6 +466,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
       pv(ob, vtf, pf_b);
       if (more) load_v(r + 1);
     }
+    return NB;
+  };
+  auto generic_tile = [&](const int T) __attribute__((always_inline)) {
+    const int r = generic_blocks(T, 0, std::true_type{});
+    if (r < NB) generic_blocks(T, r, std::false_type{});
   };
 
   // Leading tiles that need no mask for this wave: complete, and (causal) entirely at or below
@@ -507,8 +529,14 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   }
   for (; T < nkt; ++T) {
     if (T + 1 < nkt) copy_all(T + 1);
+    // The barrier publishes the next tile and releases this tile's stage for the tile after the next.  The item's
+    // last tile but one has no such successor, so the waves that work on it here pass the barrier first: the waves
+    // for which that tile needed no mask (the lower half of a causal query tile) then start on the last tile
+    // without waiting for this one, and the two diagonal tiles are worked on side by side.
+    const bool barrier_first = T + 2 == nkt;
+    if (barrier_first) end_of_tile();
     generic_tile(T);
-    end_of_tile();
+    if (!barrier_first) end_of_tile();
   }
   mfma_result_fence();
 

@@ -34,6 +34,11 @@ __device__ __forceinline__ void mfma_next_b_agpr(f32x16& acc, const bf16x8& a, c
 __device__ __forceinline__ void mfma_acc_agpr(f32x16& acc, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
+// The same for compiler-scheduled code, where the instruction in front may be a move INTO the accumulator that the
+// compiler placed there (it does not know that the statement reads it as an MFMA's C operand: two wait states).
+__device__ __forceinline__ void mfma_acc_agpr_after_moves(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
 // Pins the compiler's own memory instructions (LDS reads) to this point of the sequence.
 __device__ __forceinline__ void asm_fence() { asm volatile("" ::: "memory"); }
 __device__ __forceinline__ void mfma_result_fence() { asm volatile("s_nop 15\n\ts_nop 3" ::: "memory"); }
