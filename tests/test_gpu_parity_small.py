@@ -9,6 +9,17 @@ from parity_util import compare_all, randn_bf16, run_gpu, to64
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def persistent_kernels():
+    """At head dimension 128 the library would pick the kernels with 128-row work items for most shapes of this file
+    (short sequences); the tests that call it directly are about the 256-row persistent kernels and their work queues,
+    so those are fixed here.  `case` runs both item sizes itself."""
+    from paper_2401_09149_amd import binding
+    binding.ie_attn_set_tile_rows(256)
+    yield
+    binding.ie_attn_set_tile_rows(0)
+
+
 def case(oracle, B, S, Hq, Hkv, D, causal=True, cu=None, seed=0, scale=None, grad_abs_tol=None):
     scale = D ** -0.5 if scale is None else scale
     q = randn_bf16((B, S, Hq, D), seed)
@@ -125,9 +136,11 @@ def test_late_outlier_keys_move_the_reference(oracle):
     v = randn_bf16((B, S, H, D), 133)
     do = randn_bf16((B, S, H, D), 134)
     scale = D ** -0.5
-    got = run_gpu(q, k, v, do, scale, True, None)
+    from paper_2401_09149_amd import binding
     ref = oracle.attn_fwd_bwd(to64(q), to64(k), to64(v), to64(do), scale, True, None)
-    compare_all(got, ref, "late outliers", grad_abs_tol=30 * 5e-2)
+    for rows in (256, 128):
+        binding.ie_attn_set_tile_rows(rows)
+        compare_all(run_gpu(q, k, v, do, scale, True, None), ref, f"late outliers rows{rows}", grad_abs_tol=30 * 5e-2)
 
 
 def test_backward_is_bitwise_reproducible_and_phases_compose():

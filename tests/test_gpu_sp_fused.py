@@ -16,6 +16,16 @@ pytestmark = pytest.mark.gpu
     (1, 8192, 32, 32, 128, 4, True),   # the paper's own plan for 7B at 32K (s_sp = 4: 8 heads per GPU), full size
 ])
 def test_fused_calls_equal_unpack_attention_pack(B, Sl, Hq, Hkv, D, P, causal):
+    from paper_2401_09149_amd import binding
+    try:
+        for rows in ((256, 128) if D == 128 else (0,)):   # both sizes of the forward's and dQ's work items
+            binding.ie_attn_set_tile_rows(rows)
+            _fused_against_unfused(B, Sl, Hq, Hkv, D, P, causal)
+    finally:
+        binding.ie_attn_set_tile_rows(0)
+
+
+def _fused_against_unfused(B, Sl, Hq, Hkv, D, P, causal):
     import torch
     from paper_2401_09149_amd import binding
     dev = "cuda:0"
