@@ -427,7 +427,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   // This lane's key (column of S); clamped copies are computed but never written.
   int64_t key = k0 + wv * 32 + n;
   const bool key_ok = key < tc.doc_end;
-  const int64_t key_ld = key_ok ? key : tc.doc_end - 1;
   const int key_rel = (int)(key - q_begin);  // position of the key among the rows that see the tile
   // dS workspace (STORE_DS): this lane's 32-byte slot inside the block of the step's (query head, query
   // tile), for 32-query block 0 (block rb adds 2048); the block itself is located once per step (ds_step)
@@ -438,11 +437,32 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(AttnParams p
   char* ds_first = STORE_DS ? reinterpret_cast<char*>(p.ds) + ds_matrix_offset(p.S / BQ, (int64_t)tc.b * p.Hq + g * group, it0, p.causal != 0)
                             : nullptr;   // first step of the current query head
   char* ds_step = ds_first;
+  // The item's K and V rows reach their registers through the second LDS stage, which is free until the first step
+  // copies the second query tile into it: two coalesced tile copies and one 16-byte LDS read per fragment.  (Loaded
+  // straight from memory, a fragment instruction gathers 32 bytes from each of 32 rows: 2.7 us per item for the 16 of
+  // them against 1 us for the copies.)  Keys past the document's end repeat its last key, as key_ld does.
   bf16x8 kf[NKS], vf[NKS];                   // live in AGPRs
+  {
+    AsyncTile<D> ldk;
+    ldk.init(tid, kv_pitch);
+    const int keys = (int)((tc.doc_end - k0 < BK) ? tc.doc_end - k0 : BK);   // >= 1
+    const char* ksrc = reinterpret_cast<const char*>(p.k) + kvhead + kv_row_off(k0);
+    const char* vsrc = reinterpret_cast<const char*>(p.v) + kvhead + kv_row_off(k0);
 #pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) {
-    kf[ks] = global_load_to_agpr(reinterpret_cast<const char*>(p.k) + kvhead + kv_row_off(key_ld) + (ks * 16 + h * 8) * 2);
-    vf[ks] = global_load_to_agpr(reinterpret_cast<const char*>(p.v) + kvhead + kv_row_off(key_ld) + (ks * 16 + h * 8) * 2);
+    for (int part = 0; part < BK / 64; ++part) {
+      const int first = keys > 64 * part ? 64 * part : keys - 1;
+      const int valid = keys > 64 * part ? keys - 64 * part : 1;
+      ldk.load(lds0 + STAGE_BYTES + part * 64 * ROW_BYTES, ksrc + (int64_t)first * kv_pitch, valid);
+      ldk.load(lds0 + STAGE_BYTES + TILE_BYTES + part * 64 * ROW_BYTES, vsrc + (int64_t)first * kv_pitch, valid);
+    }
+    async_wait_all();
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      const uint32_t a = lds0 + STAGE_BYTES + (uint32_t)(wv * 32 * ROW_BYTES) + (uint32_t)tile_off<D>(n, 2 * ks + h);
+      kf[ks] = lds_load_to_agpr(a);
+      vf[ks] = lds_load_to_agpr(a + TILE_BYTES);
+    }
   }
 
   // Per-lane LDS addresses for each stage; block, tile and k-step offsets are immediates.

@@ -131,6 +131,12 @@ __device__ __forceinline__ bf16x8 global_load_to_agpr(const void* ptr) {
   asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(r) : "v"(ptr) : "memory");
   return r;
 }
+// The same from LDS (byte address `lds_addr`, 16-byte aligned).
+__device__ __forceinline__ bf16x8 lds_load_to_agpr(uint32_t lds_addr) {
+  bf16x8 r;
+  asm volatile("ds_read_b128 %0, %1" : "=a"(r) : "v"(lds_addr) : "memory");
+  return r;
+}
 // A fragment computed in VGPRs, moved into accumulation registers through a lane-private
 // 16-byte LDS slot (`lds_addr`, 16-byte aligned): there is no 128-bit VGPR->AGPR move, and a
 // value the compiler itself holds is copied over again before every assembly use.  A wave's
