@@ -324,3 +324,61 @@ def test_forward_and_backward_can_be_captured_in_a_graph_and_replayed():
             torch.cuda.synchronize()
             for got, ref in zip((o, lse, dq, dk, dv), want):
                 assert torch.equal(got, ref), (fast, trial)
+
+
+_PIN_ALL_SLOTS = r"""
+import sys
+import torch
+sys.path.insert(0, {root!r})
+from paper_2401_09149_amd import binding
+dev = "cuda:0"
+B, S, H, D = 1, 512, 2, 128
+binding.ie_attn_set_tile_rows(256)
+g = torch.Generator().manual_seed(77)
+q, k, v = (torch.randn((B, S, H, D), generator=g).to(torch.bfloat16).to(dev) for _ in range(3))
+scale = D ** -0.5
+o_ref, lse_ref = binding.attn_fwd(q, k, v, scale, True, None)
+torch.cuda.synchronize()
+outs = [(torch.empty_like(o_ref), torch.empty_like(lse_ref)) for _ in range(260)]
+codes = []
+graph = torch.cuda.CUDAGraph()
+with torch.cuda.graph(graph):
+    for o, lse in outs:
+        try:
+            binding.ie_attn_fwd(q, k, v, o, lse, None, scale, True)
+            codes.append(0)
+        except binding.IeAttnError as e:
+            codes.append(e.code)
+graph.replay()
+torch.cuda.synchronize()
+ok = sum(c == 0 for c in codes)
+assert ok == 256, codes.count(0)                       # one slot per captured call, for good
+assert all(c == -7 for c in codes[256:]), codes[256:]  # the others: IE_ERR_BUSY, nothing launched, the capture intact
+for (o, lse), c in zip(outs, codes):
+    if c == 0:
+        assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+try:
+    binding.attn_fwd(q, k, v, scale, True, None)        # eager calls find no slot either from now on
+    raise SystemExit("an eager call got a slot that a captured graph holds")
+except binding.IeAttnError as e:
+    assert e.code == -7
+binding.ie_attn_set_tile_rows(128)                      # the 128-row forward needs no slot
+o2, lse2 = binding.attn_fwd(q, k, v, scale, True, None)
+torch.cuda.synchronize()
+assert (o2.float() - o_ref.float()).abs().max() < 2e-2
+print("pinned", ok)
+"""
+
+
+def test_captured_forward_calls_pin_their_slots_and_the_rest_get_ie_err_busy():
+    """A forward call recorded under stream capture keeps its work-queue slot for the life of the process (the host
+    cannot see a graph's replays).  With all 256 slots held that way every further call of the 256-row forward must
+    fail with IE_ERR_BUSY before launching anything, under capture and eagerly, and the graph must still replay
+    correctly.  Run in a process of its own, which it leaves without slots."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", _PIN_ALL_SLOTS.format(root=root)], capture_output=True, text=True, timeout=280)
+    print(r.stdout[-2000:], r.stderr[-2000:], flush=True)
+    assert r.returncode == 0 and "pinned 256" in r.stdout
