@@ -25,13 +25,13 @@
  *     buffers.  The library allocates no device memory and never synchronises with the host: all
  *     work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and the buffers must stay alive until the stream has passed it.
- *     Calls may overlap on different streams.  The kernels are persistent and draw their work from eight
- *     counters per launch, which a one-wave kernel clears on `stream` in front of the main kernel.  The
- *     backward kernels keep them in the caller's workspace: two backward calls that overlap must not share a
- *     workspace.  ie_attn_fwd (head dimension 128) takes them from 256 slots of a device array inside the
- *     library; a slot is handed out again only when the event recorded behind its previous launch has
- *     completed, or to a launch on the same stream, and when every slot is in flight on other streams the
- *     call returns IE_ERR_BUSY rather than share one.
+ *     Calls may overlap on different streams.  The main kernels are persistent and draw their work from a few
+ *     counters per launch.  The backward kernels keep them in the caller's workspace, where the call's first
+ *     kernel clears them: two backward calls that overlap must not share a workspace.  ie_attn_fwd (head
+ *     dimension 128, 256-row items) takes them from 256 slots of a device array inside the library, which
+ *     every launch leaves cleared; a slot is handed out again only when the event recorded behind its
+ *     previous launch has completed, or to a launch on the same stream, and when every slot is in flight on
+ *     other streams the call returns IE_ERR_BUSY rather than share one.
  *     A call enqueues kernel launches only (no memset, no copy, no allocation), so it may be recorded
  *     under stream capture; a forward call captured into a graph keeps its counter slot for the life of
  *     the process (at most 256 such calls), and two replays of one graph must not run at the same time.

@@ -40,6 +40,9 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_delta_kernel(AttnParams p) 
   extern __shared__ float s_delta[];       // [Hq][tokens per workgroup]
   const int kTok = p.tiles;                // tokens per workgroup
   const int tid = threadIdx.x;
+  // The work-queue counters of the two kernels that follow on this stream (tile_queue.hpp) are cleared here, which
+  // saves each of them a launch of its own in front.
+  if (blockIdx.x == 0 && tid < 2 * (kQueueBytes / 4)) p.ws_counters[tid] = 0u;
   const int sub = tid % LPR, rloc = tid / LPR;
   const int64_t blocks_per_batch = (p.S + kTok - 1) / kTok;
   const int64_t b = blockIdx.x / blocks_per_batch;
@@ -985,6 +988,7 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     attn_bwd_delta_kernel<D><<<dim3((unsigned)grid), dim3(kThreads), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
   }
+  const bool cleared_by_delta = (phases & 1) != 0;   // the delta kernel of this call clears both queues' counters
   // With room for dS in the workspace (p.ds), dK/dV runs first and stores it, and dQ is one product.
   const bool from_ds = p.ds != nullptr;
   auto dq_phase = [&]() -> int {
@@ -1000,7 +1004,7 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
         int per_cu = 1;
         int rc = kernel_setup(setup, attn_bwd_dq_from_ds_kernel<D>, smem, &per_cu);
         if (rc) return rc;
-        const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st);
+        const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st, cleared_by_delta);
         if (ql.err != hipSuccess) return hip_fail(ql.err);
         attn_bwd_dq_from_ds_kernel<D><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
@@ -1017,7 +1021,7 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
       tiles = tiles_per_head(p.S, DqCfg<W>::BM, p.cu, p.num_docs);
       items = tiles * p.B * p.Hq;
       a.tiles = (int32_t)tiles;
-      const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st);
+      const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDq, items, a.Hq, per_cu, st, cleared_by_delta);
       if (ql.err != hipSuccess) return hip_fail(ql.err);
       attn_bwd_dq_kernel<D, W><<<dim3((unsigned)ql.grid), dim3(64 * W), smem, st>>>(a);
       if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
@@ -1040,7 +1044,7 @@ static int launch_bwd_d(AttnParams p, int phases, hipStream_t st) {
     if (items >= ((int64_t)1 << 31)) return kErrShape;
     AttnParams a = p;
     a.tiles = (int32_t)tiles;
-    const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDkdv, items, a.Hkv, per_cu, st);
+    const QueueLaunch ql = tile_queue_prepare(a, p.ws_counters + kCountersDkdv, items, a.Hkv, per_cu, st, cleared_by_delta);
     if (ql.err != hipSuccess) return hip_fail(ql.err);
     attn_bwd_dkdv_kernel<D, kStore, kChunked><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);

@@ -554,6 +554,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd_wide_kernel(AttnParams p
   store(oa, sa, k_begin + rel_a, ok_a);
   store(ob, sb, k_begin + rel_b, ok_b);
   }  // next item
+  queue_leave(&s_work);
 }
 
 // ---- counter slots of the forward's work queue ------------------------------------------------
@@ -662,12 +663,13 @@ int launch_fwd_wide(AttnParams p, hipStream_t st) {
   unsigned int* counters = nullptr;
   bool capturing = false;
   if ((rc = slot_acquire(st, &dev, &slot, &counters, &capturing)) != 0) return rc;
-  const QueueLaunch ql = tile_queue_prepare(p, counters, items, p.Hq, 1, st);
+  // (the slot's counters are zeros: they start out so, and every launch leaves them so, see queue_leave)
+  const QueueLaunch ql = tile_queue_prepare(p, counters, items, p.Hq, 1, st, true);
   if (ql.err != hipSuccess) { slot_release(dev, slot, st, capturing, false); return hip_fail(ql.err); }
   if (chunked) attn_fwd_wide_kernel<true><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
   else attn_fwd_wide_kernel<false><<<dim3((unsigned)ql.grid), dim3(kThreads), smem, st>>>(p);
   hipError_t e = hipGetLastError();
-  slot_release(dev, slot, st, capturing, true);   // (the reset kernel is enqueued either way)
+  slot_release(dev, slot, st, capturing, e == hipSuccess);   // (a launch that failed has enqueued nothing: the counters are untouched)
   return e == hipSuccess ? 0 : hip_fail(e);
 }
 

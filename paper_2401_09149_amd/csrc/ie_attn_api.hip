@@ -19,7 +19,7 @@ constexpr int64_t kMaxElems = (int64_t)1 << 40;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// One [B,Hq,S] fp32 plane of the backward workspace; and its counter area (tile_queue.hpp: 32 bytes per kernel).
+// One [B,Hq,S] fp32 plane of the backward workspace; and its counter area (tile_queue.hpp: kQueueBytes per kernel).
 size_t stat_bytes(int64_t B, int64_t S, int32_t Hq) { return align_up((size_t)B * (size_t)Hq * (size_t)S * sizeof(float), 256); }
 constexpr size_t kCounterBytes = 256;
 

@@ -10,10 +10,12 @@
 // that the workgroups of an XCD still stream the same head's K/V through its L2 together), and a
 // workgroup whose list is empty takes from the next XCD's list.
 //
-// The eight counters of a launch (32 bytes, `AttnParams::q_counters`) are memory that belongs to
+// The counters of a launch (kQueueBytes, `AttnParams::q_counters`) are memory that belongs to
 // that launch alone: the backward kernels take them from the caller's workspace, the forward from
-// a pool of slots whose use the host tracks with events (attn_fwd_wide.hip).  A one-wave kernel on
-// the same stream clears them in front of the main kernel.
+// a pool of slots whose use the host tracks with events (attn_fwd_wide.hip).  They have to be zeros when the main
+// kernel starts: the backward's are cleared by the call's first kernel (or, when a call runs single kernels, by a
+// one-wave kernel in front of each), the forward's slots start out as zeros and are left so by every launch
+// (queue_leave).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -24,10 +26,10 @@
 
 namespace ie {
 
-constexpr int kQueueBytes = 32;   // 8 counters
+constexpr int kQueueBytes = 64;   // 8 list counters, one counter of workgroups that have left (queue_leave), padding
 
 static __global__ void tile_queue_reset_kernel(unsigned int* counters) {
-  if (threadIdx.x < 8) counters[threadIdx.x] = 0u;
+  if (threadIdx.x < kQueueBytes / 4) counters[threadIdx.x] = 0u;
 }
 
 // The XCD this wave runs on (0..7).
@@ -69,6 +71,19 @@ __device__ __forceinline__ int next_work(const AttnParams& p, QueueState* s_work
   return (int)uniform((uint32_t)s_work->work);
 }
 
+// For launches whose counters are NOT cleared in front of them (the forward's slots, which start out as zeros): every
+// workgroup calls this once, after its last next_work(); the last one to do so, which knows that nobody will touch the
+// counters again, clears them for the slot's next launch.
+__device__ __forceinline__ void queue_leave(QueueState* s_work) {
+  if (threadIdx.x == 0) {
+    unsigned int* c = s_work->counters;
+    if (atomicAdd(c + 8, 1u) == gridDim.x - 1) {
+#pragma unroll
+      for (int i = 0; i < 9; ++i) __hip_atomic_store(c + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 // Per kernel and device: the dynamic LDS limit is raised once, and the number of workgroups of `kernel`
 // that fit on one CU together (registers, LDS; at least 1) is asked once.
 struct KernelSetup { std::atomic<int> per_cu[kMaxDevices]; };
@@ -89,10 +104,11 @@ static inline int kernel_setup(KernelSetup& ks, K kernel, int smem_bytes, int* p
 }
 
 // Host side: fills the queue fields of `p` for `total` items (= tiles per head x B x heads) with the
-// launch's own `counters` (device memory, 32 bytes) and clears them on `st`.  Returns the grid size for
+// launch's own `counters` (device memory, kQueueBytes) and clears them on `st` (unless they are clear already).  Returns the grid size for
 // `per_cu` resident workgroups per CU.
 struct QueueLaunch { int grid; hipError_t err; };
-static inline QueueLaunch tile_queue_prepare(AttnParams& p, unsigned int* counters, int64_t total, int heads, int per_cu, hipStream_t st) {
+static inline QueueLaunch tile_queue_prepare(AttnParams& p, unsigned int* counters, int64_t total, int heads, int per_cu, hipStream_t st,
+                                             bool already_clear = false) {
   QueueLaunch r{0, hipSuccess};
   const int cus = cu_count(&r.err);
   if (r.err != hipSuccess) return r;
@@ -103,8 +119,11 @@ static inline QueueLaunch tile_queue_prepare(AttnParams& p, unsigned int* counte
   p.q_heavy = p.tiles - p.tiles * 3 / 8;   // (at 4K-16K the split makes no measurable difference; at 32K 0 % and 30 % are 1-4 % slower)
   const int64_t want = (int64_t)cus * per_cu;
   r.grid = (int)(total < want ? total : want);
-  tile_queue_reset_kernel<<<1, 64, 0, st>>>(counters);
-  r.err = hipGetLastError();
+  // (`already_clear`: a kernel in front of this launch on the same stream has cleared the counters)
+  if (!already_clear) {
+    tile_queue_reset_kernel<<<1, 64, 0, st>>>(counters);
+    r.err = hipGetLastError();
+  }
   return r;
 }
 
