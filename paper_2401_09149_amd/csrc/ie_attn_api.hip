@@ -185,7 +185,7 @@ int ie_attn_bwd_static(const void* q, const void* k, const void* v, const void* 
     ptr = g_scratch_ptr[dev];
   }
   // Every byte the kernels read from the array is written earlier in the same call (the delta kernel fills both
-  // planes for all B*Hq*S rows, the reset kernels clear the counters), so nothing has to be cleared here.
+  // planes for all B*Hq*S rows and clears the work-queue counters), so nothing has to be cleared here.
   return ie_attn_bwd_phases(q, k, v, o, dout, lse, dq, dk, dv, cu_seqlens, num_docs, B, S, Hq, Hkv, D, scale, causal,
                             ptr, kStaticBytes, IE_BWD_ALL, stream);
 }
