@@ -167,6 +167,17 @@ def test_plan_shape_7b_s4k_b2_h32(oracle):
     check_identities(cfg, cu, gpu_in, gpu_out)
 
 
+def test_head_dim_64_s8k_gqa_ragged(oracle):
+    # head dimension 64 takes kernels of its own (128-row items, compiler-scheduled): many key tiles, a ragged last tile,
+    # two query heads per kv head, every element of both kv heads against the oracle
+    from paper_2401_09149_amd import workloads as W
+    cfg = W.AttnConfig("d64_s8269_hq4_hkv2", 16, B=1, S=8192 + 77, Hq=4, Hkv=2, D=64)
+    cu, cpu_in, gpu_in, gpu_out = run_full(cfg)
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 0)
+    check_head(oracle, cfg, cu, cpu_in, gpu_out, 1)
+    check_identities(cfg, cu, gpu_in, gpu_out)
+
+
 def test_config2_s128k_h8(oracle):
     from paper_2401_09149_amd import workloads as W
     cfg = W.CONFIGS[2]
