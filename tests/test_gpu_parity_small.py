@@ -382,3 +382,23 @@ def test_captured_forward_calls_pin_their_slots_and_the_rest_get_ie_err_busy():
     r = subprocess.run([sys.executable, "-c", _PIN_ALL_SLOTS.format(root=root)], capture_output=True, text=True, timeout=280)
     print(r.stdout[-2000:], r.stderr[-2000:], flush=True)
     assert r.returncode == 0 and "pinned 256" in r.stdout
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(oracle, seed):
+    """Shapes, head groupings, masks and document splits drawn from a seeded generator: whatever combination of ragged
+    tiles, empty and one-token documents, batches and head groups comes up, every element against the oracle."""
+    rng = np.random.default_rng(9000 + seed)
+    D = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    Hq = Hkv * int(rng.choice([1, 2, 4]))
+    causal = bool(rng.integers(0, 2))
+    if rng.integers(0, 3) == 0:   # packed documents, B = 1
+        lens = rng.integers(0, 400, size=int(rng.integers(1, 9)))
+        lens[rng.integers(0, len(lens))] += 1   # at least one token
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        case(oracle, 1, int(cu[-1]), Hq, Hkv, D, causal=causal, cu=cu, seed=9100 + seed)
+    else:
+        B = int(rng.choice([1, 2, 3]))
+        S = int(rng.integers(1, 900))
+        case(oracle, B, S, Hq, Hkv, D, causal=causal, seed=9100 + seed)
